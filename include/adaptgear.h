@@ -1,0 +1,202 @@
+/*
+ * adaptgear.h -- C ABI of the MI355X (gfx950) neighbour-aggregation library.
+ *
+ * The library implements the hot path of AdaptGear (arXiv 2305.17408): the
+ * GNN aggregate-sum operator  Y = A.H  and its backward  dH = A^T.G  in fp32,
+ * where A is an N x N sparse (normalised) adjacency matrix whose rows are
+ * destination vertices and whose columns are source vertices (paper Sec. 2.1,
+ * "Graph Format"), and H is a dense row-major N x F feature matrix.
+ *
+ * Following the paper's design (Sec. 3), a plan reorders the vertices by
+ * communities once on the CPU, decomposes the matrix into an intra-community
+ * subgraph (diagonal blocks) and an inter-community subgraph (the remainder),
+ * runs each with a kernel suited to its density (Sec. 3.2), and picks the
+ * kernel set by timing the candidates during the first calls (Sec. 3.3).
+ *
+ * Conventions
+ *   - every function returns AG_OK (0) or a negative AG_ERR_* code and never
+ *     aborts; ag_last_error() gives a thread-local message for the last error;
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory of the current device, fp32 row-major, 16-byte aligned;
+ *   - a plan owns its device topology; feature matrices stay owned by the caller;
+ *   - work is enqueued on the caller's HIP stream and the call returns without
+ *     waiting, except during the selector's trial calls (which read events);
+ *   - calls on one plan (and on its clones) must not overlap in time: they
+ *     share scratch memory for partial sums of very long rows.
+ */
+#ifndef ADAPTGEAR_H
+#define ADAPTGEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AG_OK               0
+#define AG_ERR_INVALID     -1   /* bad argument or malformed matrix            */
+#define AG_ERR_NOMEM       -2   /* host or device allocation failed            */
+#define AG_ERR_HIP         -3   /* a HIP runtime call failed                   */
+#define AG_ERR_UNSUPPORTED -4   /* valid request this build cannot serve       */
+
+typedef struct ag_plan ag_plan;   /* opaque */
+
+/* Sparse matrix in CSR form, HOST memory, borrowed only during ag_plan_create.
+ * rowptr is monotone with rowptr[0] = 0 and rowptr[n] = nnz; column indices lie in
+ * [0, n); rows may be unsorted (they are sorted); a repeated (row, col) pair is an
+ * error.  vals == NULL means unit weights (the weight-free sum of Algorithm 1). */
+typedef struct {
+    int64_t        n;
+    int64_t        nnz;
+    const int32_t *rowptr;   /* n + 1 */
+    const int32_t *colidx;   /* nnz, source vertex of each entry */
+    const float   *vals;     /* nnz or NULL */
+} ag_csr;
+
+/* vertex order of the feature matrices passed to ag_aggregate* */
+#define AG_LAYOUT_ORIGINAL  0   /* caller's numbering; the library permutes in and out   */
+#define AG_LAYOUT_REORDERED 1   /* rows already in plan order (see ag_permute_rows)      */
+
+#define AG_FLAG_HOST_ONLY   1   /* build the decomposition on the host only: no device   *
+                                 * memory, ag_aggregate* return AG_ERR_UNSUPPORTED       */
+
+/* All fields optional: zero selects the default. */
+typedef struct {
+    int32_t block_cap;      /* largest community / diagonal block, 1..128 (default 128; the   *
+                             * paper used 16, Sec. 2.3)                                        */
+    int32_t min_block;      /* communities smaller than this go to the block-less tail (16)    */
+    int32_t sweeps;         /* label-propagation sweeps per level (8)                          */
+    int32_t max_levels;     /* coarsening levels (12)                                          */
+    int32_t trials;         /* timed runs per candidate in the selector (3)                    */
+    int32_t layout;         /* AG_LAYOUT_*                                                     */
+    int32_t flags;          /* AG_FLAG_*                                                       */
+    float   dense_density;  /* blocks at least this dense may use the dense kernel (0.20)      */
+    void *(*dev_alloc)(size_t bytes, void *user);   /* default hipMalloc                       */
+    void  (*dev_free)(void *ptr, void *user);       /* default hipFree                         */
+    void   *user;
+} ag_options;
+
+/* ---- plan life cycle -------------------------------------------------------------------- */
+
+/* Reorder (Sec. 2.2, Sec. 4.2 stage 1), decompose (Sec. 3.3, Sec. 4.2 stage 2), build the
+ * per-kernel formats and upload them.  `N` must equal A->n; `F` (>= 1) is the feature width
+ * the plan will be called with.  On success *out receives a new plan. */
+int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt, ag_plan **out);
+
+/* A second plan for feature width F2 that shares the topology (host and device) of `p`;
+ * it has its own selector state.  Destroy both; the topology goes with the last one. */
+int ag_plan_clone_for_width(const ag_plan *p, int32_t F2, ag_plan **out);
+
+void ag_plan_destroy(ag_plan *p);
+
+/* ---- the hot path ----------------------------------------------------------------------- */
+
+/* Y = A.H (aggregate-sum of Sec. 2.1 with an edge value).  H, Y: device, N x F, Y is
+ * overwritten and must not alias H. */
+int ag_aggregate(ag_plan *p, const float *H_dev, float *Y_dev, void *hip_stream);
+
+/* dH = A^T.G, the backward of ag_aggregate (training, Sec. 5 "Benchmarks"). */
+int ag_aggregate_t(ag_plan *p, const float *G_dev, float *dH_dev, void *hip_stream);
+
+/* dst[new] = src[perm[new]] (inverse == 0: caller order -> plan order) or
+ * dst[perm[new]] = src[new] (inverse != 0).  N x F device matrices, no aliasing. */
+int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int32_t F,
+                    int32_t inverse, void *hip_stream);
+
+/* ---- kernel selection (Sec. 3.3 "Adaptive Selector") ------------------------------------ */
+
+/* subgraph classes */
+#define AG_CLS_BLOCKS_DENSE   0   /* diagonal blocks with density >= dense_density          */
+#define AG_CLS_BLOCKS_SPARSE  1   /* all other diagonal blocks                               */
+#define AG_CLS_REMAINDER      2   /* inter-community subgraph (+ tail rows)                  */
+#define AG_CLS_COMPOSE        3   /* how the pieces are combined                             */
+#define AG_NUM_CLS            4
+
+/* kernels for the two block classes */
+#define AG_K_BLOCK_SPARSE     0   /* block CSR with features staged in LDS (Sec. 3.2, CSR intra) */
+#define AG_K_BLOCK_DENSE      1   /* dense tile on fp32 MFMA (Sec. 3.2, dense-based kernel)       */
+/* kernels for the remainder: lanes cooperating on one row */
+#define AG_K_CSR_NARROW       0   /* one feature-wide lane group per row (Sec. 3.2, CSR inter)    */
+#define AG_K_CSR_WIDE         1   /* several lane groups per row, neighbours interleaved          */
+/* compositions */
+#define AG_COMPOSE_SPLIT      0   /* block kernels write Y, the remainder kernel accumulates      */
+#define AG_COMPOSE_FUSED      1   /* sparse-block kernel also walks its rows' remainder           */
+#define AG_COMPOSE_FULL_CSR   2   /* no decomposition at run time: one CSR over the whole matrix  */
+
+#define AG_DIR_FWD 0
+#define AG_DIR_BWD 1
+
+/* Pin the kernel of class `cls` for direction `dir`; kernel_id = -1 returns the class to the
+ * adaptive selector (and restarts its trials). */
+int ag_plan_force_kernels(ag_plan *p, int32_t cls, int32_t dir, int32_t kernel_id);
+
+typedef struct {
+    int32_t frozen;                 /* 1 once the trials are over                              */
+    int32_t calls;                  /* calls seen for this direction                           */
+    int32_t choice[AG_NUM_CLS];     /* current kernel id per class                             */
+    float   trial_ms[AG_NUM_CLS][4];/* median time of each candidate (ms), <0 = not measured   */
+    float   total_trial_ms;         /* wall time spent inside trial calls                      */
+} ag_selector_info;
+
+int ag_plan_selector_info(const ag_plan *p, int32_t dir, ag_selector_info *out);
+
+/* ---- inspection (tests, reports) -------------------------------------------------------- */
+
+/* Host views of the decomposition, owned by the plan, valid until it is destroyed.
+ * perm[new] = old, iperm[old] = new; diagonal block b covers plan rows
+ * [blk_ptr[b], blk_ptr[b+1]); rows from blk_ptr[n_blocks] on are the tail.  The two CSR
+ * parts are in plan numbering, columns ascending, values carried over unchanged. */
+typedef struct {
+    int64_t n, nnz_intra, nnz_inter;
+    int32_t n_blocks;
+    const int32_t *perm, *iperm, *blk_ptr;
+    const int32_t *intra_rowptr, *intra_col; const float *intra_val;   /* val NULL if unit */
+    const int32_t *inter_rowptr, *inter_col; const float *inter_val;
+} ag_export;
+
+int ag_plan_export(const ag_plan *p, ag_export *out);
+
+typedef struct {
+    int64_t n, nnz, nnz_intra, nnz_inter;
+    int32_t F, n_blocks, n_block_rows, n_dense_blocks, symmetric, unit_weights;
+    int64_t n_long_rows, n_long_segments;      /* remainder rows split across wavefronts     */
+    double  density_full, density_intra, density_inter;  /* cf. the paper's density figure   */
+    double  sec_reorder, sec_split, sec_build, sec_upload;
+    int64_t device_bytes;                      /* topology held on the device                */
+} ag_stats;
+
+int ag_plan_stats(const ag_plan *p, ag_stats *out);
+
+const char *ag_last_error(void);
+
+/* ---- model-step drivers ----------------------------------------------------------------- */
+
+/* GIN sum aggregation (Sec. 2.1 aggregate-sum, Sec. 5): Y = A.H + eps*H, where the stored
+ * pattern already holds the unit diagonal ((1+eps) self term); ag_gin_layer_t is its backward. */
+int ag_gin_layer  (ag_plan *p, float eps, const float *H_dev, float *Y_dev, void *hip_stream);
+int ag_gin_layer_t(ag_plan *p, float eps, const float *G_dev, float *dH_dev, void *hip_stream);
+
+/* Two-layer GCN training step (Sec. 5 "Benchmarks"), forward + backward, no optimiser update:
+ *   P = A.X; H1 = relu(P W1 + b1); Q = H1 W2; Z = A.Q + b2; loss = mean softmax-CE(Z, labels)
+ *   dZ; dQ = A^T dZ; dW2 = H1^T dQ; db2; dH1 = dQ W2^T; dPre = dH1 * (H1 > 0); dW1 = P^T dPre; db1
+ * All matrices device fp32 row-major in PLAN order (AG_LAYOUT_REORDERED plans only).
+ * p_in is a plan of width f_in, p_out one of width n_class (clones of one topology).
+ * The workspace is caller-provided device memory of at least ag_gcn_workspace_bytes(). */
+typedef struct {
+    int32_t f_in, hidden, n_class;
+    const float *W1, *b1, *W2, *b2;        /* device: f_in x hidden, hidden, hidden x n_class, n_class */
+    float *dW1, *db1, *dW2, *db2;          /* device outputs, same shapes                              */
+    float *loss;                           /* device, 1 float                                          */
+    float *logits;                         /* device N x n_class output (Z), may be NULL               */
+} ag_gcn_io;
+
+size_t ag_gcn_workspace_bytes(int64_t n, int32_t f_in, int32_t hidden, int32_t n_class);
+int ag_gcn_step(ag_plan *p_in, ag_plan *p_out, const ag_gcn_io *io, const float *X_dev,
+                const int32_t *labels_dev, void *workspace_dev, size_t workspace_bytes,
+                void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAPTGEAR_H */

@@ -1,0 +1,126 @@
+// Internal declarations shared by the translation units of libadaptgear.
+#pragma once
+#include <cstdint>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "adaptgear.h"
+
+namespace ag {
+
+constexpr int kMaxBlock   = 128;   // rows of a diagonal block; LDS tiles are sized for it
+constexpr int kLongThresh = 96;    // remainder rows above this many entries are split ...
+constexpr int kSegLen     = 384;   // ... into segments of this many entries, one wavefront each
+
+// ----------------------------------------------------------------------------------------
+// host-side matrices
+// ----------------------------------------------------------------------------------------
+struct HostCsr {
+    int64_t n = 0;
+    std::vector<int32_t> rowptr;   // n + 1
+    std::vector<int32_t> col;
+    std::vector<float>   val;      // empty when unit weights
+    int64_t nnz() const { return rowptr.empty() ? 0 : rowptr.back(); }
+};
+
+// Integer-weighted undirected graph used by the multilevel reordering.
+struct WGraph {
+    int32_t n = 0;
+    std::vector<int64_t> xadj;
+    std::vector<int32_t> adj, ew, nw;
+};
+
+struct ReorderResult {
+    std::vector<int32_t> perm, iperm, blk_ptr, comm;
+    int32_t n_blocks = 0;
+};
+
+// reorder.cpp
+void build_pattern_graph(const HostCsr &A, const HostCsr &At, WGraph &g);
+void community_reorder(const WGraph &g0, int32_t cap, int32_t min_block, int32_t sweeps,
+                       int32_t max_levels, ReorderResult &out);
+
+// decompose.cpp
+int  ingest_csr(const ag_csr *in, HostCsr &out, std::string &err);       // validate + sort rows
+void transpose_csr(const HostCsr &A, HostCsr &At);
+bool bitwise_equal(const HostCsr &A, const HostCsr &B);
+void permute_and_split(const HostCsr &A, const ReorderResult &r, HostCsr &full, HostCsr &intra,
+                       HostCsr &inter);
+
+// One direction (forward = A, backward = A^T) of the decomposed matrix, in plan numbering.
+struct HostDir {
+    HostCsr full, intra, inter;
+    // long-row segmentation of a CSR part: rows with more than kLongThresh entries
+    struct Segs {
+        std::vector<int32_t> seg_row, seg_beg, seg_end;   // one entry per segment
+        std::vector<int32_t> lr_row, lr_seg0;             // per long row: row id, first segment (nlr+1)
+    } segs_full, segs_inter;
+    std::vector<uint8_t>  intra_col8;      // block-local column of every intra entry
+    std::vector<uint32_t> bitmap;          // per dense-class block: 128 rows x 4 words
+    std::vector<float>    tiles;           // per dense-class block: 4 x 64 x 64 floats (weighted only)
+};
+
+void build_segments(const HostCsr &A, HostDir::Segs &s);
+void build_block_formats(const ReorderResult &r, const std::vector<int32_t> &dense_blocks,
+                         bool unit, HostDir &d);
+
+// ----------------------------------------------------------------------------------------
+// device-side views (plain pointers, passed to kernels by value)
+// ----------------------------------------------------------------------------------------
+struct CsrDev {
+    const int32_t *rowptr = nullptr, *col = nullptr;
+    const float   *val = nullptr;          // nullptr = unit weights
+    int32_t n = 0;
+    const int32_t *seg_row = nullptr, *seg_beg = nullptr, *seg_end = nullptr;
+    int32_t nseg = 0;
+    const int32_t *lr_row = nullptr, *lr_seg0 = nullptr;
+    int32_t nlr = 0;
+};
+
+struct BlocksDev {
+    const int32_t *blk_ptr = nullptr;      // nb + 1
+    int32_t nb = 0, n_block_rows = 0;
+    const int32_t *i_rowptr = nullptr;     // n_block_rows + 1 (intra entries of block rows)
+    const uint8_t *i_col8 = nullptr;
+    const float   *i_val = nullptr;        // nullptr = unit weights
+    const int32_t *list_dense = nullptr, *list_sparse = nullptr, *list_all = nullptr;
+    int32_t n_dense = 0, n_sparse = 0;
+    const uint32_t *bitmap = nullptr;      // n_dense x 128 x 4
+    const float    *tiles = nullptr;       // n_dense x 16384, nullptr = unit weights
+};
+
+struct DevDir {
+    CsrDev full, inter;
+    BlocksDev blk;
+};
+
+// kernels_csr.hip
+// Rows [row_begin,row_end) of `A`: rows below `acc_below` add to Y, the others overwrite it.
+// `wide` selects several lane groups per row.  Long rows are left to launch_csr_long.
+int launch_csr_rows(const CsrDev &A, const float *H, float *Y, int32_t F, int32_t row_begin,
+                    int32_t row_end, int32_t acc_below, bool wide, void *stream);
+// All long rows of `A`: segments -> partial[nseg][F] -> Y (rows below acc_below accumulate).
+int launch_csr_long(const CsrDev &A, const float *H, float *Y, int32_t F, float *partial,
+                    int32_t acc_below, void *stream);
+// kernels_block.hip
+int launch_block_sparse(const BlocksDev &B, const int32_t *list, int32_t nlist, const CsrDev *fused_rem,
+                        const float *H, float *Y, int32_t F, void *stream);
+// kernels_dense.hip
+int launch_block_dense(const BlocksDev &B, const float *H, float *Y, int32_t F, void *stream);
+// kernels_misc.hip
+int launch_permute_rows(const int32_t *perm, int64_t n, int32_t F, const float *src, float *dst,
+                        bool inverse, void *stream);
+int launch_axpy(int64_t count, float a, const float *x, float *y, void *stream);
+int launch_bias_relu(int64_t n, int32_t f, const float *bias, float *M, void *stream);
+int launch_softmax_xent(int64_t n, int32_t c, const float *Zin, const float *bias,
+                        const int32_t *labels, float *Zout, float *dZ, float *rowloss, void *stream);
+int launch_relu_grad(int64_t count, const float *act, float *grad, void *stream);
+size_t col_sum_scratch_floats(int32_t f);
+int launch_col_sum(int64_t n, int32_t f, const float *M, float *out, float *scratch, void *stream);
+int launch_fill_zero(int64_t count, float *p, void *stream);
+
+void set_error(const std::string &msg);
+int  hip_fail(int hip_error_code, const char *what);
+
+}  // namespace ag

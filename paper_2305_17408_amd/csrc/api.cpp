@@ -1,0 +1,604 @@
+// Plan life cycle, kernel composition and the adaptive selector (paper Sec. 3.1, Sec. 3.3).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+
+#include "ag_internal.h"
+
+namespace ag {
+
+static thread_local std::string g_err;
+void set_error(const std::string &msg) { g_err = msg; }
+int hip_fail(int code, const char *what)
+{
+    if (code == (int)hipSuccess) return AG_OK;
+    g_err = std::string(what) + ": " + hipGetErrorString((hipError_t)code);
+    return AG_ERR_HIP;
+}
+
+namespace {
+
+double now_sec()
+{
+    using namespace std::chrono;
+    return duration<double>(steady_clock::now().time_since_epoch()).count();
+}
+
+void *default_alloc(size_t bytes, void *)
+{
+    void *p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+    return p;
+}
+void default_free(void *p, void *) { (void)hipFree(p); }
+
+}  // namespace
+
+// Everything that depends only on the matrix: shared by a plan and its width clones.
+struct Topology {
+    ag_options opt{};
+    int64_t n = 0, nnz = 0;
+    bool unit = false, symmetric = false, host_only = false;
+    ReorderResult r;
+    HostDir h[2];                       // h[1] is filled only for non-symmetric matrices
+    std::vector<int32_t> dense_blocks, sparse_blocks, all_blocks;
+    DevDir d[2];
+    const int32_t *perm_dev = nullptr;
+    std::vector<void *> owned;          // device allocations
+    int64_t device_bytes = 0;
+    double sec_reorder = 0, sec_split = 0, sec_build = 0, sec_upload = 0;
+    int64_t max_segments = 0;
+
+    ~Topology()
+    {
+        for (void *p : owned) opt.dev_free(p, opt.user);
+    }
+
+    void *dalloc(size_t bytes)
+    {
+        void *p = opt.dev_alloc(bytes ? bytes : 16, opt.user);
+        if (p) {
+            owned.push_back(p);
+            device_bytes += (int64_t)bytes;
+        }
+        return p;
+    }
+
+    template <class T>
+    int upload(const std::vector<T> &v, const T *&out)
+    {
+        out = nullptr;
+        void *p = dalloc(v.size() * sizeof(T));
+        if (!p) { set_error("device allocation failed"); return AG_ERR_NOMEM; }
+        if (!v.empty()) {
+            int rc = hip_fail((int)hipMemcpy(p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice), "upload");
+            if (rc) return rc;
+        }
+        out = (const T *)p;
+        return AG_OK;
+    }
+
+    int upload_csr(const HostCsr &A, const HostDir::Segs &s, CsrDev &D)
+    {
+        int rc;
+        D.n = (int32_t)A.n;
+        if ((rc = upload(A.rowptr, D.rowptr))) return rc;
+        if ((rc = upload(A.col, D.col))) return rc;
+        if (!A.val.empty()) { if ((rc = upload(A.val, D.val))) return rc; }
+        if ((rc = upload(s.seg_row, D.seg_row))) return rc;
+        if ((rc = upload(s.seg_beg, D.seg_beg))) return rc;
+        if ((rc = upload(s.seg_end, D.seg_end))) return rc;
+        if ((rc = upload(s.lr_row, D.lr_row))) return rc;
+        if ((rc = upload(s.lr_seg0, D.lr_seg0))) return rc;
+        D.nseg = (int32_t)s.seg_row.size();
+        D.nlr = (int32_t)s.lr_row.size();
+        max_segments = std::max<int64_t>(max_segments, D.nseg);
+        return AG_OK;
+    }
+
+    int upload_dir(int k, const int32_t *blk_ptr_dev, const int32_t *ld, const int32_t *ls, const int32_t *la)
+    {
+        HostDir &H = h[k];
+        DevDir &D = d[k];
+        int rc;
+        if ((rc = upload_csr(H.full, H.segs_full, D.full))) return rc;
+        if ((rc = upload_csr(H.inter, H.segs_inter, D.inter))) return rc;
+        BlocksDev &B = D.blk;
+        B.blk_ptr = blk_ptr_dev;
+        B.nb = r.n_blocks;
+        B.n_block_rows = r.blk_ptr.back();
+        std::vector<int32_t> irp(H.intra.rowptr.begin(), H.intra.rowptr.begin() + B.n_block_rows + 1);
+        if ((rc = upload(irp, B.i_rowptr))) return rc;
+        if ((rc = upload(H.intra_col8, B.i_col8))) return rc;
+        if (!H.intra.val.empty()) { if ((rc = upload(H.intra.val, B.i_val))) return rc; }
+        B.list_dense = ld; B.list_sparse = ls; B.list_all = la;
+        B.n_dense = (int32_t)dense_blocks.size();
+        B.n_sparse = (int32_t)sparse_blocks.size();
+        if ((rc = upload(H.bitmap, B.bitmap))) return rc;
+        if (!unit && B.n_dense > 0) { if ((rc = upload(H.tiles, B.tiles))) return rc; }
+        return AG_OK;
+    }
+};
+
+// Feedback-driven kernel selection for one direction (Sec. 3.3): during the first calls every
+// candidate runs 1 warm-up + `trials` timed times with events around each subgraph kernel;
+// afterwards the fastest candidate per subgraph class is kept.  A second round compares the
+// ways of composing the pieces by their total time.
+struct Selector {
+    int forced[AG_NUM_CLS];
+    int choice[AG_NUM_CLS];
+    int ncand[AG_NUM_CLS];
+    int phase = 0;          // 0: per-class trials, 1: composition trials, 2: frozen
+    int cand = 0, rep = 0, calls = 0;
+    std::vector<float> samples[AG_NUM_CLS][4];
+    float median_ms[AG_NUM_CLS][4];
+    float total_trial_ms = 0.f;
+
+    void reset(bool keep_forced)
+    {
+        for (int c = 0; c < AG_NUM_CLS; ++c) {
+            if (!keep_forced) forced[c] = -1;
+            choice[c] = 0;
+            for (int k = 0; k < 4; ++k) { samples[c][k].clear(); median_ms[c][k] = -1.f; }
+        }
+        phase = 0; cand = 0; rep = 0; total_trial_ms = 0.f;
+    }
+};
+
+}  // namespace ag
+
+using namespace ag;
+
+struct ag_plan {
+    std::shared_ptr<Topology> topo;
+    int32_t F = 0, layout = 0, trials = 3;
+    float *partial = nullptr;            // long-row partial sums: max_segments x F
+    float *tmp_in = nullptr, *tmp_out = nullptr;   // AG_LAYOUT_ORIGINAL staging, n x F each
+    Selector sel[2];
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    std::vector<void *> owned;
+
+    ~ag_plan()
+    {
+        for (auto &e : ev) if (e) (void)hipEventDestroy(e);
+        if (topo) for (void *p : owned) topo->opt.dev_free(p, topo->opt.user);
+    }
+};
+
+namespace {
+
+static float median_of(std::vector<float> v)
+{
+    if (v.empty()) return -1.f;
+    std::sort(v.begin(), v.end());
+    return v[v.size() / 2];
+}
+
+void init_selector(ag_plan *p, int dir, bool keep_forced)
+{
+    Selector &s = p->sel[dir];
+    s.reset(keep_forced);
+    const Topology &t = *p->topo;
+    s.ncand[AG_CLS_BLOCKS_DENSE] = t.dense_blocks.empty() ? 1 : 2;
+    s.ncand[AG_CLS_BLOCKS_SPARSE] = 1;
+    s.ncand[AG_CLS_REMAINDER] = 2;
+    s.ncand[AG_CLS_COMPOSE] = (t.r.n_blocks > 0) ? 3 : 1;
+}
+
+int plan_device_buffers(ag_plan *p)
+{
+    Topology &t = *p->topo;
+    if (t.host_only) return AG_OK;
+    auto take = [&](size_t bytes) -> float * {
+        void *q = t.opt.dev_alloc(bytes ? bytes : 16, t.opt.user);
+        if (q) p->owned.push_back(q);
+        return (float *)q;
+    };
+    p->partial = take((size_t)t.max_segments * p->F * sizeof(float));
+    if (!p->partial) { set_error("device allocation failed (partials)"); return AG_ERR_NOMEM; }
+    if (p->layout == AG_LAYOUT_ORIGINAL) {
+        p->tmp_in = take((size_t)t.n * p->F * sizeof(float));
+        p->tmp_out = take((size_t)t.n * p->F * sizeof(float));
+        if (!p->tmp_in || !p->tmp_out) { set_error("device allocation failed (staging)"); return AG_ERR_NOMEM; }
+    }
+    return AG_OK;
+}
+
+// Enqueue one aggregation with a fixed kernel choice.  `ev` (4 events) may be null.
+int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, hipStream_t st,
+               hipEvent_t *ev)
+{
+    const Topology &t = *p->topo;
+    const DevDir &D = t.d[dir_idx];
+    const int32_t F = p->F, n = (int32_t)t.n, nbr = D.blk.n_block_rows;
+    const bool wide = k[AG_CLS_REMAINDER] == AG_K_CSR_WIDE;
+    int rc = AG_OK;
+    if (ev) (void)hipEventRecord(ev[0], st);
+    switch (k[AG_CLS_COMPOSE]) {
+    case AG_COMPOSE_FULL_CSR:
+        if (ev) { (void)hipEventRecord(ev[1], st); (void)hipEventRecord(ev[2], st); }
+        if ((rc = launch_csr_rows(D.full, H, Y, F, 0, n, 0, wide, st))) return rc;
+        if ((rc = launch_csr_long(D.full, H, Y, F, p->partial, 0, st))) return rc;
+        break;
+    case AG_COMPOSE_FUSED:
+        if ((rc = launch_block_sparse(D.blk, D.blk.list_all, D.blk.nb, &D.inter, H, Y, F, st))) return rc;
+        if (ev) { (void)hipEventRecord(ev[1], st); (void)hipEventRecord(ev[2], st); }
+        if ((rc = launch_csr_rows(D.inter, H, Y, F, nbr, n, 0, wide, st))) return rc;
+        if ((rc = launch_csr_long(D.inter, H, Y, F, p->partial, nbr, st))) return rc;
+        break;
+    default:
+        if (k[AG_CLS_BLOCKS_DENSE] == AG_K_BLOCK_DENSE)
+            rc = launch_block_dense(D.blk, H, Y, F, st);
+        else
+            rc = launch_block_sparse(D.blk, D.blk.list_dense, D.blk.n_dense, nullptr, H, Y, F, st);
+        if (rc) return rc;
+        if (ev) (void)hipEventRecord(ev[1], st);
+        if ((rc = launch_block_sparse(D.blk, D.blk.list_sparse, D.blk.n_sparse, nullptr, H, Y, F, st))) return rc;
+        if (ev) (void)hipEventRecord(ev[2], st);
+        if ((rc = launch_csr_rows(D.inter, H, Y, F, 0, n, nbr, wide, st))) return rc;
+        if ((rc = launch_csr_long(D.inter, H, Y, F, p->partial, nbr, st))) return rc;
+        break;
+    }
+    if (ev) (void)hipEventRecord(ev[3], st);
+    return AG_OK;
+}
+
+int fastest(Selector &s, int c)
+{
+    int best = -1;
+    for (int k = 0; k < s.ncand[c]; ++k) {
+        s.median_ms[c][k] = median_of(s.samples[c][k]);
+        if (s.median_ms[c][k] >= 0 && (best < 0 || s.median_ms[c][k] < s.median_ms[c][best])) best = k;
+    }
+    return best < 0 ? 0 : best;                        // ties and "nothing measured" -> lowest id
+}
+
+void finish_phase0(Selector &s)
+{
+    for (int c = 0; c < AG_CLS_COMPOSE; ++c) s.choice[c] = s.forced[c] >= 0 ? s.forced[c] : fastest(s, c);
+}
+
+void finish_phase1(Selector &s)
+{
+    const int c = AG_CLS_COMPOSE;
+    s.choice[c] = s.forced[c] >= 0 ? s.forced[c] : fastest(s, c);
+}
+
+// Decide what this call runs; returns true when the call is a timed trial.
+bool next_choice(ag_plan *p, Selector &s, int *k)
+{
+    for (;;) {
+        if (s.phase == 0) {
+            int maxc = 1;
+            bool any_free = false;
+            for (int c = 0; c < AG_CLS_COMPOSE; ++c)
+                if (s.forced[c] < 0 && s.ncand[c] > 1) { maxc = std::max(maxc, s.ncand[c]); any_free = true; }
+            if (!any_free || s.cand >= maxc) {
+                finish_phase0(s);
+                s.phase = 1; s.cand = 0; s.rep = 0;
+                continue;
+            }
+            for (int c = 0; c < AG_CLS_COMPOSE; ++c)
+                k[c] = s.forced[c] >= 0 ? s.forced[c] : std::min(s.cand, s.ncand[c] - 1);
+            k[AG_CLS_COMPOSE] = (p->topo->r.n_blocks > 0) ? AG_COMPOSE_SPLIT : AG_COMPOSE_FULL_CSR;
+            return true;
+        }
+        if (s.phase == 1) {
+            const int c = AG_CLS_COMPOSE;
+            if (s.forced[c] >= 0 || s.ncand[c] <= 1 || s.cand >= s.ncand[c]) {
+                finish_phase1(s);
+                if (s.ncand[c] <= 1) s.choice[c] = AG_COMPOSE_FULL_CSR;
+                s.phase = 2;
+                continue;
+            }
+            for (int q = 0; q < AG_CLS_COMPOSE; ++q) k[q] = s.choice[q];
+            k[c] = s.cand;
+            return true;
+        }
+        for (int q = 0; q < AG_NUM_CLS; ++q) k[q] = s.choice[q];
+        return false;
+    }
+}
+
+void record_trial(ag_plan *p, Selector &s, const int *k, hipEvent_t *ev)
+{
+    float ms[4] = {0, 0, 0, 0};
+    (void)hipEventSynchronize(ev[3]);
+    (void)hipEventElapsedTime(&ms[0], ev[0], ev[1]);
+    (void)hipEventElapsedTime(&ms[1], ev[1], ev[2]);
+    (void)hipEventElapsedTime(&ms[2], ev[2], ev[3]);
+    (void)hipEventElapsedTime(&ms[3], ev[0], ev[3]);
+    s.total_trial_ms += ms[3];
+    const bool timed = s.rep > 0;                       // rep 0 is the warm-up
+    if (timed) {
+        if (s.phase == 0) {
+            for (int c = 0; c < AG_CLS_COMPOSE; ++c)
+                if (s.forced[c] < 0 && s.cand < s.ncand[c]) s.samples[c][k[c]].push_back(ms[c]);
+        } else {
+            s.samples[AG_CLS_COMPOSE][k[AG_CLS_COMPOSE]].push_back(ms[3]);
+        }
+    }
+    if (++s.rep > p->trials) { s.rep = 0; ++s.cand; }
+}
+
+int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
+{
+    if (!p || !X || !Y) { set_error("null argument"); return AG_ERR_INVALID; }
+    if (X == Y) { set_error("input and output must not alias"); return AG_ERR_INVALID; }
+    Topology &t = *p->topo;
+    if (t.host_only) { set_error("plan was created with AG_FLAG_HOST_ONLY"); return AG_ERR_UNSUPPORTED; }
+    if (t.n == 0) return AG_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int dir_idx = (dir == AG_DIR_BWD && !t.symmetric) ? 1 : 0;
+    Selector &s = p->sel[dir];
+    const float *in = X;
+    float *out = Y;
+    int rc;
+    if (p->layout == AG_LAYOUT_ORIGINAL) {
+        if ((rc = launch_permute_rows(t.perm_dev, t.n, p->F, X, p->tmp_in, false, st))) return rc;
+        in = p->tmp_in;
+        out = p->tmp_out;
+    }
+    int k[AG_NUM_CLS];
+    ++s.calls;
+    const bool trial = next_choice(p, s, k);
+    if (trial && !p->ev[0])
+        for (auto &e : p->ev)
+            if ((rc = hip_fail((int)hipEventCreate(&e), "event create"))) return rc;
+    if ((rc = run_choice(p, dir_idx, k, in, out, st, trial ? p->ev : nullptr))) return rc;
+    if (trial) record_trial(p, s, k, p->ev);
+    if (p->layout == AG_LAYOUT_ORIGINAL)
+        if ((rc = launch_permute_rows(t.perm_dev, t.n, p->F, p->tmp_out, Y, true, st))) return rc;
+    return AG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ag_last_error(void) { return g_err.c_str(); }
+
+int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_in, ag_plan **out)
+{
+    if (!out) { set_error("out is null"); return AG_ERR_INVALID; }
+    *out = nullptr;
+    if (!A || A->n != N) { set_error("N does not match the matrix"); return AG_ERR_INVALID; }
+    if (F < 1) { set_error("F must be at least 1"); return AG_ERR_INVALID; }
+    ag_options o{};
+    if (opt_in) o = *opt_in;
+    if (o.block_cap == 0) o.block_cap = kMaxBlock;
+    if (o.min_block == 0) o.min_block = 16;
+    if (o.sweeps == 0) o.sweeps = 8;
+    if (o.max_levels == 0) o.max_levels = 12;
+    if (o.trials == 0) o.trials = 3;
+    if (o.dense_density == 0.f) o.dense_density = 0.20f;
+    if (o.block_cap < 1 || o.block_cap > kMaxBlock || o.min_block < 1 || o.sweeps < 1 || o.max_levels < 1 ||
+        o.trials < 1 || (o.layout != AG_LAYOUT_ORIGINAL && o.layout != AG_LAYOUT_REORDERED) ||
+        (!o.dev_alloc) != (!o.dev_free)) {
+        set_error("option out of range");
+        return AG_ERR_INVALID;
+    }
+    if (!o.dev_alloc) { o.dev_alloc = default_alloc; o.dev_free = default_free; }
+    try {
+        auto t = std::make_shared<Topology>();
+        t->opt = o;
+        t->host_only = (o.flags & AG_FLAG_HOST_ONLY) != 0;
+        HostCsr A0, At;
+        std::string err;
+        int rc = ingest_csr(A, A0, err);
+        if (rc) { set_error(err); return rc; }
+        t->n = A0.n;
+        t->nnz = A0.nnz();
+        t->unit = A0.val.empty();
+        double t0 = now_sec();
+        transpose_csr(A0, At);
+        t->symmetric = bitwise_equal(A0, At);
+        {
+            WGraph g;
+            build_pattern_graph(A0, At, g);
+            community_reorder(g, o.block_cap, o.min_block, o.sweeps, o.max_levels, t->r);
+        }
+        double t1 = now_sec();
+        t->sec_reorder = t1 - t0;
+        permute_and_split(A0, t->r, t->h[0].full, t->h[0].intra, t->h[0].inter);
+        if (!t->symmetric) permute_and_split(At, t->r, t->h[1].full, t->h[1].intra, t->h[1].inter);
+        double t2 = now_sec();
+        t->sec_split = t2 - t1;
+        // density classes (decided on the forward matrix; the transpose has the same counts)
+        const HostCsr &I = t->h[0].intra;
+        for (int32_t b = 0; b < t->r.n_blocks; ++b) {
+            const int32_t r0 = t->r.blk_ptr[b], r1 = t->r.blk_ptr[b + 1];
+            const double sz = r1 - r0, cnt = I.rowptr[r1] - I.rowptr[r0];
+            t->all_blocks.push_back(b);
+            if (cnt >= o.dense_density * sz * sz && sz >= 32) t->dense_blocks.push_back(b);
+            else t->sparse_blocks.push_back(b);
+        }
+        const int ndir = t->symmetric ? 1 : 2;
+        for (int k = 0; k < ndir; ++k) {
+            build_segments(t->h[k].full, t->h[k].segs_full);
+            build_segments(t->h[k].inter, t->h[k].segs_inter);
+            build_block_formats(t->r, t->dense_blocks, t->unit, t->h[k]);
+        }
+        double t3 = now_sec();
+        t->sec_build = t3 - t2;
+        if (!t->host_only) {
+            const int32_t *bp = nullptr, *ld = nullptr, *ls = nullptr, *la = nullptr;
+            if ((rc = t->upload(t->r.blk_ptr, bp))) return rc;
+            if ((rc = t->upload(t->dense_blocks, ld))) return rc;
+            if ((rc = t->upload(t->sparse_blocks, ls))) return rc;
+            if ((rc = t->upload(t->all_blocks, la))) return rc;
+            if ((rc = t->upload(t->r.perm, t->perm_dev))) return rc;
+            for (int k = 0; k < ndir; ++k)
+                if ((rc = t->upload_dir(k, bp, ld, ls, la))) return rc;
+            if ((rc = hip_fail((int)hipDeviceSynchronize(), "upload sync"))) return rc;
+        }
+        t->sec_upload = now_sec() - t3;
+        auto *p = new ag_plan();
+        p->topo = t;
+        p->F = F;
+        p->layout = o.layout;
+        p->trials = o.trials;
+        init_selector(p, 0, false);
+        init_selector(p, 1, false);
+        if ((rc = plan_device_buffers(p))) { delete p; return rc; }
+        *out = p;
+        return AG_OK;
+    } catch (const std::bad_alloc &) {
+        set_error("host allocation failed");
+        return AG_ERR_NOMEM;
+    } catch (const std::exception &e) {
+        set_error(std::string("internal error: ") + e.what());
+        return AG_ERR_INVALID;
+    }
+}
+
+int ag_plan_clone_for_width(const ag_plan *p, int32_t F2, ag_plan **out)
+{
+    if (!p || !out || F2 < 1) { set_error("bad argument"); return AG_ERR_INVALID; }
+    *out = nullptr;
+    auto *q = new (std::nothrow) ag_plan();
+    if (!q) { set_error("host allocation failed"); return AG_ERR_NOMEM; }
+    q->topo = p->topo;
+    q->F = F2;
+    q->layout = p->layout;
+    q->trials = p->trials;
+    init_selector(q, 0, false);
+    init_selector(q, 1, false);
+    int rc = plan_device_buffers(q);
+    if (rc) { delete q; return rc; }
+    *out = q;
+    return AG_OK;
+}
+
+void ag_plan_destroy(ag_plan *p) { delete p; }
+
+int ag_aggregate(ag_plan *p, const float *H, float *Y, void *stream)
+{
+    return aggregate_dir(p, AG_DIR_FWD, H, Y, stream);
+}
+
+int ag_aggregate_t(ag_plan *p, const float *G, float *dH, void *stream)
+{
+    return aggregate_dir(p, AG_DIR_BWD, G, dH, stream);
+}
+
+int ag_permute_rows(const ag_plan *p, const float *src, float *dst, int32_t F, int32_t inverse, void *stream)
+{
+    if (!p || !src || !dst || F < 1 || src == dst) { set_error("bad argument"); return AG_ERR_INVALID; }
+    if (p->topo->host_only) { set_error("host-only plan"); return AG_ERR_UNSUPPORTED; }
+    return launch_permute_rows(p->topo->perm_dev, p->topo->n, F, src, dst, inverse != 0, stream);
+}
+
+int ag_plan_force_kernels(ag_plan *p, int32_t cls, int32_t dir, int32_t kernel_id)
+{
+    if (!p || cls < 0 || cls >= AG_NUM_CLS || (dir != AG_DIR_FWD && dir != AG_DIR_BWD)) {
+        set_error("bad class or direction");
+        return AG_ERR_INVALID;
+    }
+    static const int limit[AG_NUM_CLS] = {2, 1, 2, 3};
+    if (kernel_id < -1 || kernel_id >= 4) { set_error("kernel id out of range"); return AG_ERR_INVALID; }
+    if (kernel_id >= limit[cls]) { set_error("kernel id not available for this class"); return AG_ERR_UNSUPPORTED; }
+    Selector &s = p->sel[dir];
+    const int keep[AG_NUM_CLS] = {s.forced[0], s.forced[1], s.forced[2], s.forced[3]};
+    init_selector(p, dir, false);
+    for (int c = 0; c < AG_NUM_CLS; ++c) s.forced[c] = keep[c];
+    s.forced[cls] = kernel_id;
+    if (p->topo->r.n_blocks == 0) s.forced[AG_CLS_COMPOSE] = AG_COMPOSE_FULL_CSR;
+    return AG_OK;
+}
+
+int ag_plan_selector_info(const ag_plan *p, int32_t dir, ag_selector_info *out)
+{
+    if (!p || !out || (dir != AG_DIR_FWD && dir != AG_DIR_BWD)) { set_error("bad argument"); return AG_ERR_INVALID; }
+    const Selector &s = p->sel[dir];
+    out->frozen = s.phase == 2;
+    out->calls = s.calls;
+    for (int c = 0; c < AG_NUM_CLS; ++c) {
+        out->choice[c] = s.choice[c];
+        for (int k = 0; k < 4; ++k) out->trial_ms[c][k] = s.median_ms[c][k];
+    }
+    out->total_trial_ms = s.total_trial_ms;
+    return AG_OK;
+}
+
+int ag_plan_export(const ag_plan *p, ag_export *out)
+{
+    if (!p || !out) { set_error("bad argument"); return AG_ERR_INVALID; }
+    const Topology &t = *p->topo;
+    const HostDir &h = t.h[0];
+    out->n = t.n;
+    out->nnz_intra = h.intra.nnz();
+    out->nnz_inter = h.inter.nnz();
+    out->n_blocks = t.r.n_blocks;
+    out->perm = t.r.perm.data();
+    out->iperm = t.r.iperm.data();
+    out->blk_ptr = t.r.blk_ptr.data();
+    out->intra_rowptr = h.intra.rowptr.data();
+    out->intra_col = h.intra.col.data();
+    out->intra_val = t.unit ? nullptr : h.intra.val.data();
+    out->inter_rowptr = h.inter.rowptr.data();
+    out->inter_col = h.inter.col.data();
+    out->inter_val = t.unit ? nullptr : h.inter.val.data();
+    return AG_OK;
+}
+
+int ag_plan_stats(const ag_plan *p, ag_stats *out)
+{
+    if (!p || !out) { set_error("bad argument"); return AG_ERR_INVALID; }
+    const Topology &t = *p->topo;
+    std::memset(out, 0, sizeof(*out));
+    out->n = t.n;
+    out->nnz = t.nnz;
+    out->nnz_intra = t.h[0].intra.nnz();
+    out->nnz_inter = t.h[0].inter.nnz();
+    out->F = p->F;
+    out->n_blocks = t.r.n_blocks;
+    out->n_block_rows = t.r.blk_ptr.back();
+    out->n_dense_blocks = (int32_t)t.dense_blocks.size();
+    out->symmetric = t.symmetric;
+    out->unit_weights = t.unit;
+    out->n_long_rows = (int64_t)t.h[0].segs_inter.lr_row.size();
+    out->n_long_segments = (int64_t)t.h[0].segs_inter.seg_row.size();
+    const double nn = (double)t.n * (double)t.n;
+    double blk_area = 0;
+    for (int32_t b = 0; b < t.r.n_blocks; ++b) {
+        const double s = t.r.blk_ptr[b + 1] - t.r.blk_ptr[b];
+        blk_area += s * s;
+    }
+    out->density_full = nn > 0 ? (double)t.nnz / nn : 0;
+    out->density_intra = blk_area > 0 ? (double)out->nnz_intra / blk_area : 0;
+    out->density_inter = nn - blk_area > 0 ? (double)out->nnz_inter / (nn - blk_area) : 0;
+    out->sec_reorder = t.sec_reorder;
+    out->sec_split = t.sec_split;
+    out->sec_build = t.sec_build;
+    out->sec_upload = t.sec_upload;
+    out->device_bytes = t.device_bytes;
+    return AG_OK;
+}
+
+int ag_gin_layer(ag_plan *p, float eps, const float *H, float *Y, void *stream)
+{
+    int rc = aggregate_dir(p, AG_DIR_FWD, H, Y, stream);
+    if (rc || eps == 0.f) return rc;
+    return launch_axpy(p->topo->n * (int64_t)p->F, eps, H, Y, stream);
+}
+
+int ag_gin_layer_t(ag_plan *p, float eps, const float *G, float *dH, void *stream)
+{
+    int rc = aggregate_dir(p, AG_DIR_BWD, G, dH, stream);
+    if (rc || eps == 0.f) return rc;
+    return launch_axpy(p->topo->n * (int64_t)p->F, eps, G, dH, stream);
+}
+
+}  // extern "C"
+
+// accessors for gcn.cpp
+namespace ag {
+int64_t plan_n(const ag_plan *p) { return p->topo->n; }
+int32_t plan_f(const ag_plan *p) { return p->F; }
+int32_t plan_layout(const ag_plan *p) { return p->layout; }
+bool plan_same_topology(const ag_plan *a, const ag_plan *b) { return a->topo == b->topo; }
+bool plan_host_only(const ag_plan *p) { return p->topo->host_only; }
+}  // namespace ag

@@ -1,0 +1,103 @@
+// Device helpers shared by the aggregation kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "ag_internal.h"
+
+namespace ag {
+
+constexpr int kWG = 256;   // work-group size of every aggregation kernel (4 wavefronts)
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(const float *__restrict__ p, float (&h)[VEC])
+{
+    if constexpr (VEC == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        h[0] = t.x; h[1] = t.y; h[2] = t.z; h[3] = t.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) h[j] = p[j];
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float *__restrict__ p, const float (&h)[VEC])
+{
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<float4 *>(p) = make_float4(h[0], h[1], h[2], h[3]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) p[j] = h[j];
+    }
+}
+
+// Work-groups are handed to the 8 XCDs round-robin.  This maps the hardware block id to a
+// logical id such that each XCD walks one contiguous eighth of the logical range, so rows
+// that share neighbours (same community) meet in the same L2.
+__device__ __forceinline__ int xcd_contiguous(int bid, int nb)
+{
+    const int x = bid & 7, i = bid >> 3, per = nb >> 3, rem = nb & 7;
+    return x * per + (x < rem ? x : rem) + i;
+}
+
+// Accumulate entries [beg,end) of one CSR row into acc.  A team of W lanes (W/G lane groups
+// of G lanes, each lane owning VEC features starting at column f) loads W (column, value)
+// pairs at a time, hands them round with lane shuffles, and every lane group gathers the
+// feature rows of its share of the entries.  All W lanes of the team must call this together.
+template <int G, int W, int VEC>
+__device__ __forceinline__ void team_row_gather(const int32_t *__restrict__ col,
+                                                const float *__restrict__ val, int beg, int end,
+                                                const float *__restrict__ H, int F, int f, bool fok,
+                                                int tl, float (&acc)[VEC])
+{
+    constexpr int NSG = W / G, U = 4;
+    const int sg = tl / G;
+    for (int base = beg; base < end; base += W) {
+        const int e = base + tl;
+        int c = 0;
+        float v = 0.f;
+        if (e < end) {
+            c = col[e];
+            v = val ? val[e] : 1.f;
+        }
+        const int cnt = min(W, end - base);
+        for (int k0 = 0; k0 < cnt; k0 += NSG * U) {
+            int ck[U];
+            float vk[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int kk = k0 + u * NSG + sg;
+                ck[u] = __shfl(c, kk & (W - 1), W);
+                vk[u] = __shfl(v, kk & (W - 1), W);
+            }
+            float h[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int kk = k0 + u * NSG + sg;
+                if (kk < cnt && fok) {
+                    load_vec<VEC>(H + (size_t)ck[u] * F + f, h[u]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) h[u][j] = 0.f;
+                    vk[u] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] = fmaf(vk[u], h[u][j], acc[j]);
+        }
+    }
+}
+
+// Sum the partial accumulators of the W/G lane groups of a team; every group ends with the total.
+template <int G, int W, int VEC>
+__device__ __forceinline__ void team_reduce(float (&acc)[VEC])
+{
+#pragma unroll
+    for (int off = G; off < W; off <<= 1)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] += __shfl_xor(acc[j], off, W);
+}
+
+}  // namespace ag

@@ -1,0 +1,163 @@
+// CSR-based kernel for low, irregular density (paper Sec. 3.2 "CSR-based kernel", the
+// inter-community case): rows are mapped to lane teams, every lane walks source neighbours
+// and gathers their feature rows straight from global memory.  Differences from the paper's
+// CUDA mapping: the topology of a row is fetched once by the team and passed between lanes
+// with wave shuffles instead of through shared memory; one row is served by a group of lanes
+// that covers the feature width with 16-byte loads (one or several groups per row); rows
+// above a degree threshold are cut into segments, one wavefront each, whose partial sums are
+// combined by a second kernel in a fixed order (no atomics, bitwise reproducible).
+#include "kernels_common.h"
+
+namespace ag {
+namespace {
+
+template <int G, int W, int VEC>
+__global__ __launch_bounds__(kWG) void k_csr_rows(CsrDev A, const float *__restrict__ H,
+                                                  float *__restrict__ Y, int F, int row_begin,
+                                                  int row_end, int acc_below)
+{
+    constexpr int TEAMS = kWG / W;
+    const int tid = threadIdx.x;
+    const int team = tid / W, tl = tid % W, gl = tl % G;
+    const int wg = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int row = row_begin + wg * TEAMS + team;
+    if (row >= row_end) return;                       // the whole team leaves together
+    const int beg = A.rowptr[row], end = A.rowptr[row + 1];
+    if (end - beg > kLongThresh) return;              // served by the segment kernels
+    const int f = blockIdx.y * (G * VEC) + gl * VEC;
+    const bool fok = f < F;
+    float acc[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+    team_row_gather<G, W, VEC>(A.col, A.val, beg, end, H, F, f, fok, tl, acc);
+    team_reduce<G, W, VEC>(acc);
+    if (tl < G && fok) {
+        float *y = Y + (size_t)row * F + f;
+        if (row < acc_below) {
+            float old[VEC];
+            load_vec<VEC>(y, old);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[j] += old[j];
+        }
+        store_vec<VEC>(y, acc);
+    }
+}
+
+// one wavefront per segment of a long row; result goes to partial[segment][F]
+template <int G, int VEC>
+__global__ __launch_bounds__(kWG) void k_csr_segments(CsrDev A, const float *__restrict__ H,
+                                                      float *__restrict__ partial, int F)
+{
+    constexpr int W = 64;
+    const int tid = threadIdx.x;
+    const int seg = blockIdx.x * (kWG / W) + tid / W;
+    if (seg >= A.nseg) return;
+    const int tl = tid % W, gl = tl % G;
+    const int f = blockIdx.y * (G * VEC) + gl * VEC;
+    const bool fok = f < F;
+    float acc[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+    team_row_gather<G, W, VEC>(A.col, A.val, A.seg_beg[seg], A.seg_end[seg], H, F, f, fok, tl, acc);
+    team_reduce<G, W, VEC>(acc);
+    if (tl < G && fok) store_vec<VEC>(partial + (size_t)seg * F + f, acc);
+}
+
+// one lane group per long row: Y[row] (+)= sum of its segments' partials, in segment order
+template <int G, int VEC>
+__global__ __launch_bounds__(kWG) void k_csr_segment_sum(CsrDev A, const float *__restrict__ partial,
+                                                         float *__restrict__ Y, int F, int acc_below)
+{
+    const int tid = threadIdx.x;
+    const int lr = blockIdx.x * (kWG / G) + tid / G;
+    if (lr >= A.nlr) return;
+    const int f = blockIdx.y * (G * VEC) + (tid % G) * VEC;
+    if (f >= F) return;
+    const int row = A.lr_row[lr];
+    float acc[VEC];
+    float *y = Y + (size_t)row * F + f;
+    if (row < acc_below) {
+        load_vec<VEC>(y, acc);
+    } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+    }
+    for (int s = A.lr_seg0[lr]; s < A.lr_seg0[lr + 1]; ++s) {
+        float p[VEC];
+        load_vec<VEC>(partial + (size_t)s * F + f, p);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] += p[j];
+    }
+    store_vec<VEC>(y, acc);
+}
+
+struct Shape { int G, W, VEC; };
+
+// lanes per row so that a group covers min(F, tile) features with VEC-wide loads
+Shape pick_shape(int F, bool wide)
+{
+    Shape s;
+    s.VEC = (F % 4 == 0) ? 4 : 1;
+    const int need = (F + s.VEC - 1) / s.VEC, cap = (s.VEC == 4) ? 32 : 64;
+    s.G = 4;
+    while (s.G < need && s.G < cap) s.G <<= 1;
+    s.W = s.G;
+    if (wide && s.VEC == 4) s.W = (s.G >= 16) ? 64 : s.G * 4;
+    return s;
+}
+
+template <int G, int W, int VEC>
+void run_rows(const CsrDev &A, const float *H, float *Y, int F, int rb, int re, int acc_below,
+              hipStream_t st)
+{
+    const int rows = re - rb, teams = kWG / W;
+    dim3 grid((rows + teams - 1) / teams, (F + G * VEC - 1) / (G * VEC));
+    hipLaunchKernelGGL((k_csr_rows<G, W, VEC>), grid, dim3(kWG), 0, st, A, H, Y, F, rb, re, acc_below);
+}
+
+template <int G, int VEC>
+void run_long(const CsrDev &A, const float *H, float *Y, int F, float *partial, int acc_below,
+              hipStream_t st)
+{
+    const int ty = (F + G * VEC - 1) / (G * VEC);
+    hipLaunchKernelGGL((k_csr_segments<G, VEC>), dim3((A.nseg + 3) / 4, ty), dim3(kWG), 0, st, A, H,
+                       partial, F);
+    const int teams = kWG / G;
+    hipLaunchKernelGGL((k_csr_segment_sum<G, VEC>), dim3((A.nlr + teams - 1) / teams, ty), dim3(kWG),
+                       0, st, A, partial, Y, F, acc_below);
+}
+
+}  // namespace
+
+int launch_csr_rows(const CsrDev &A, const float *H, float *Y, int32_t F, int32_t row_begin,
+                    int32_t row_end, int32_t acc_below, bool wide, void *stream)
+{
+    if (row_end <= row_begin) return AG_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const Shape s = pick_shape(F, wide);
+#define AG_CASE(g, w, v) \
+    if (s.G == g && s.W == w && s.VEC == v) { run_rows<g, w, v>(A, H, Y, F, row_begin, row_end, acc_below, st); return hip_fail((int)hipGetLastError(), "csr_rows launch"); }
+    AG_CASE(4, 4, 4) AG_CASE(4, 16, 4) AG_CASE(8, 8, 4) AG_CASE(8, 32, 4)
+    AG_CASE(16, 16, 4) AG_CASE(16, 64, 4) AG_CASE(32, 32, 4) AG_CASE(32, 64, 4)
+    AG_CASE(4, 4, 1) AG_CASE(8, 8, 1) AG_CASE(16, 16, 1) AG_CASE(32, 32, 1) AG_CASE(64, 64, 1)
+#undef AG_CASE
+    set_error("csr_rows: no kernel shape for this feature width");
+    return AG_ERR_UNSUPPORTED;
+}
+
+int launch_csr_long(const CsrDev &A, const float *H, float *Y, int32_t F, float *partial,
+                    int32_t acc_below, void *stream)
+{
+    if (A.nseg == 0) return AG_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const Shape s = pick_shape(F, false);
+#define AG_CASE(g, v) \
+    if (s.G == g && s.VEC == v) { run_long<g, v>(A, H, Y, F, partial, acc_below, st); return hip_fail((int)hipGetLastError(), "csr_long launch"); }
+    AG_CASE(4, 4) AG_CASE(8, 4) AG_CASE(16, 4) AG_CASE(32, 4)
+    AG_CASE(4, 1) AG_CASE(8, 1) AG_CASE(16, 1) AG_CASE(32, 1) AG_CASE(64, 1)
+#undef AG_CASE
+    set_error("csr_long: no kernel shape for this feature width");
+    return AG_ERR_UNSUPPORTED;
+}
+
+}  // namespace ag

@@ -1,0 +1,194 @@
+// Community-based vertex reordering (paper Sec. 2.2 and Sec. 4.2, first preprocessing stage).
+//
+// The paper hands this step to an external partitioner with "community size" as its
+// parameter.  This library uses its own integer-only, deterministic method: multilevel
+// label propagation under a community-size cap.  Vertices end up grouped by community;
+// communities of at least `min_block` members become the diagonal blocks of the
+// intra-community subgraph, everything else is placed behind them as a block-less tail.
+#include <algorithm>
+#include <numeric>
+
+#include "ag_internal.h"
+
+namespace ag {
+
+// u ~ v  iff  a_uv or a_vu is stored and u != v: merge row v of A with row v of A^T.
+void build_pattern_graph(const HostCsr &A, const HostCsr &At, WGraph &g)
+{
+    const int64_t n = A.n;
+    g.n = (int32_t)n;
+    g.xadj.assign(n + 1, 0);
+    g.adj.clear();
+    g.adj.reserve((size_t)A.nnz());
+    for (int64_t v = 0; v < n; ++v) {
+        int32_t a = A.rowptr[v], ae = A.rowptr[v + 1];
+        int32_t b = At.rowptr[v], be = At.rowptr[v + 1];
+        while (a < ae || b < be) {
+            int32_t x;
+            if (b >= be || (a < ae && A.col[a] <= At.col[b])) {
+                x = A.col[a];
+                if (b < be && At.col[b] == x) ++b;
+                ++a;
+            } else {
+                x = At.col[b++];
+            }
+            if (x != v) g.adj.push_back(x);
+        }
+        g.xadj[v + 1] = (int64_t)g.adj.size();
+    }
+    g.ew.assign(g.adj.size(), 1);
+    g.nw.assign((size_t)n, 1);
+}
+
+namespace {
+
+// One level of capped label propagation; returns the cluster count and fills `cluster`
+// with dense ids numbered by first appearance in ascending node order.
+int32_t propagate(const WGraph &g, int32_t level, int32_t cap, int32_t sweeps,
+                  std::vector<int32_t> &cluster)
+{
+    const int32_t n = g.n;
+    std::vector<int32_t> label(n), size(g.nw);
+    std::vector<int64_t> tot(n, 0), conn(n, 0);
+    std::iota(label.begin(), label.end(), 0);
+    for (int32_t v = 0; v < n; ++v)
+        for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) tot[v] += g.ew[e];
+    std::vector<int32_t> touched;
+    for (int32_t s = 0; s < sweeps; ++s) {
+        int64_t moved = 0;
+        for (int32_t v = 0; v < n; ++v) {
+            if (tot[v] == 0) continue;
+            touched.clear();
+            for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) {
+                const int32_t L = label[g.adj[e]];
+                if (conn[L] == 0) touched.push_back(L);
+                conn[L] += g.ew[e];
+            }
+            const int64_t need = ((level == 0 && s == 0) || tot[v] < 2) ? 1 : 2;
+            const int32_t cur = label[v], w = g.nw[v];
+            const int64_t own = conn[cur];
+            // strongest admissible neighbouring label; equal strength -> smallest id
+            int32_t cand = -1;
+            int64_t cand_conn = 0;
+            for (int32_t L : touched) {
+                const int64_t c = conn[L];
+                conn[L] = 0;
+                if (L == cur || c < need || size[L] + w > cap) continue;
+                if (c > cand_conn || (c == cand_conn && L < cand)) { cand_conn = c; cand = L; }
+            }
+            int32_t target = cur;
+            if (own >= need) {
+                if (cand >= 0 && cand_conn > own) target = cand;      // the current label wins ties
+            } else if (cand >= 0) {
+                target = cand;                                          // weakly attached: any admissible label
+            } else if (size[cur] > w && size[v] == 0) {
+                target = v;                                             // ... or back to its own empty label
+            }
+            if (target != cur) {
+                size[cur] -= w;
+                size[target] += w;
+                label[v] = target;
+                ++moved;
+            }
+        }
+        if (!moved) break;
+    }
+    std::vector<int32_t> dense_id(n, -1);
+    int32_t k = 0;
+    cluster.resize(n);
+    for (int32_t v = 0; v < n; ++v) {
+        int32_t &d = dense_id[label[v]];
+        if (d < 0) d = k++;
+        cluster[v] = d;
+    }
+    return k;
+}
+
+// Clusters become nodes; node weights add, parallel edges add, inner edges vanish.
+void contract(const WGraph &g, const std::vector<int32_t> &cluster, int32_t k, WGraph &c)
+{
+    const int32_t n = g.n;
+    // members of every cluster, grouped by a counting sort
+    std::vector<int32_t> start(k + 1, 0), member(n);
+    for (int32_t v = 0; v < n; ++v) start[cluster[v] + 1]++;
+    for (int32_t q = 0; q < k; ++q) start[q + 1] += start[q];
+    {
+        std::vector<int32_t> at(start.begin(), start.end() - 1);
+        for (int32_t v = 0; v < n; ++v) member[at[cluster[v]]++] = v;
+    }
+    c.n = k;
+    c.nw.assign(k, 0);
+    c.xadj.assign(k + 1, 0);
+    c.adj.clear();
+    c.ew.clear();
+    std::vector<int64_t> wsum(k, 0);
+    std::vector<int32_t> seen;
+    for (int32_t q = 0; q < k; ++q) {
+        seen.clear();
+        for (int32_t m = start[q]; m < start[q + 1]; ++m) {
+            const int32_t v = member[m];
+            c.nw[q] += g.nw[v];
+            for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) {
+                const int32_t t = cluster[g.adj[e]];
+                if (t == q) continue;
+                if (wsum[t] == 0) seen.push_back(t);
+                wsum[t] += g.ew[e];
+            }
+        }
+        for (int32_t t : seen) {
+            c.adj.push_back(t);
+            c.ew.push_back((int32_t)wsum[t]);
+            wsum[t] = 0;
+        }
+        c.xadj[q + 1] = (int64_t)c.adj.size();
+    }
+}
+
+}  // namespace
+
+void community_reorder(const WGraph &g0, int32_t cap, int32_t min_block, int32_t sweeps,
+                       int32_t max_levels, ReorderResult &out)
+{
+    const int32_t n = g0.n;
+    out.comm.resize(n);
+    std::iota(out.comm.begin(), out.comm.end(), 0);
+    int32_t n_comm = n;
+    WGraph coarse;
+    const WGraph *g = &g0;
+    std::vector<int32_t> cluster;
+    for (int32_t level = 0; g->n > 0;) {
+        const int32_t k = propagate(*g, level, cap, sweeps, cluster);
+        for (int32_t v = 0; v < n; ++v) out.comm[v] = cluster[out.comm[v]];
+        n_comm = k;
+        ++level;
+        // another level only while the last one shrank the graph by at least 5 %
+        if (k == g->n || (int64_t)20 * k > (int64_t)19 * g->n || level >= max_levels) break;
+        WGraph next;
+        contract(*g, cluster, k, next);
+        coarse = std::move(next);
+        g = &coarse;
+    }
+    // layout: blocks (communities >= min_block, ascending id, members ascending), then the tail
+    std::vector<int32_t> csize(n_comm, 0), slot(n_comm, -1);
+    for (int32_t v = 0; v < n; ++v) csize[out.comm[v]]++;
+    out.blk_ptr.assign(1, 0);
+    int32_t at = 0;
+    for (int32_t c = 0; c < n_comm; ++c)
+        if (csize[c] >= min_block) {
+            slot[c] = at;
+            at += csize[c];
+            out.blk_ptr.push_back(at);
+        }
+    out.n_blocks = (int32_t)out.blk_ptr.size() - 1;
+    int32_t tail = at;
+    out.perm.resize(n);
+    out.iperm.resize(n);
+    for (int32_t v = 0; v < n; ++v) {
+        int32_t &s = slot[out.comm[v]];
+        const int32_t p = (s >= 0) ? s++ : tail++;
+        out.perm[p] = v;
+        out.iperm[v] = p;
+    }
+}
+
+}  // namespace ag

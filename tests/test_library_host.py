@@ -1,0 +1,127 @@
+"""CPU-side checks of libadaptgear: it loads, exports every declared symbol, validates its
+input, and its host decomposition (reorder + split) is bit-identical to the oracle's."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2305_17408_amd as ag
+from ag_inputs import (config_graph, planted_partition, gcn_normalise, directed_random, mixed_density,
+                       from_edges)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def host_plan(g, F=8, **kw):
+    return ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, F, flags=ag.AG_FLAG_HOST_ONLY, **kw)
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "adaptgear.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ag_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(ag.EXPORTS), declared ^ set(ag.EXPORTS)
+    L = ag.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def compare_with_oracle(g, **kw):
+    p = host_plan(g, **kw)
+    try:
+        e = ag.ag_plan_export(p)
+        okw = {k: v for k, v in kw.items() if k in ("block_cap", "min_block", "sweeps", "max_levels")}
+        r = oracle.reorder(g.rowptr, g.colidx, **okw)
+        assert np.array_equal(e["perm"], r.perm)
+        assert np.array_equal(e["iperm"], r.iperm)
+        assert np.array_equal(e["blk_ptr"], r.blk_ptr)
+        s = oracle.split(g.rowptr, g.colidx, g.vals, r.perm, r.iperm, r.blk_ptr)
+        assert np.array_equal(e["intra_rowptr"], s.intra_rowptr)
+        assert np.array_equal(e["intra_col"], s.intra_col)
+        assert np.array_equal(e["inter_rowptr"], s.inter_rowptr)
+        assert np.array_equal(e["inter_col"], s.inter_col)
+        if g.vals is not None:
+            assert np.array_equal(e["intra_val"].view(np.uint32), s.intra_val.view(np.uint32))
+            assert np.array_equal(e["inter_val"].view(np.uint32), s.inter_val.view(np.uint32))
+        else:
+            assert e["intra_val"] is None and e["inter_val"] is None
+        return ag.ag_plan_stats(p)
+    finally:
+        ag.ag_plan_destroy(p)
+
+
+def test_decomposition_bit_exact_config0_and_1():
+    st = compare_with_oracle(config_graph(0))
+    assert st["symmetric"] == 1 and st["unit_weights"] == 0 and st["nnz"] == 36864
+    st = compare_with_oracle(config_graph(1))
+    assert st["nnz_intra"] + st["nnz_inter"] == st["nnz"]
+    assert st["density_intra"] > 20 * st["density_inter"]      # cf. the paper's density figure
+
+
+@pytest.mark.parametrize("cfg,scale", [(2, 1 / 16), (3, 1 / 32), (4, 1 / 32)])
+def test_decomposition_bit_exact_scaled_configs(cfg, scale):
+    compare_with_oracle(config_graph(cfg, scale=scale))
+
+
+def test_decomposition_bit_exact_directed_and_small_caps():
+    st = compare_with_oracle(directed_random(3000, 4.0, 7), min_block=4)
+    assert st["symmetric"] == 0
+    compare_with_oracle(gcn_normalise(planted_partition(40, 16, 6, 0.8, 3)), block_cap=16, min_block=4)
+    compare_with_oracle(planted_partition(10, 100, 10, 0.9, 5), block_cap=100, min_block=1)
+    compare_with_oracle(from_edges(50, np.empty(0, int), np.empty(0, int)))
+    compare_with_oracle(from_edges(0, np.empty(0, int), np.empty(0, int)))
+
+
+def test_dense_blocks_are_classified():
+    g = mixed_density(8, 128, 0.3, 6, 0.02, 11)
+    p = host_plan(g)
+    st = ag.ag_plan_stats(p)
+    ag.ag_plan_destroy(p)
+    assert 6 <= st["n_dense_blocks"] <= 9
+    assert 0.1 < st["density_intra"] < 0.35
+
+
+def test_unsorted_rows_are_sorted_and_values_follow():
+    g = gcn_normalise(planted_partition(6, 32, 5, 0.7, 8))
+    rng = np.random.default_rng(0)
+    col, val = g.colidx.copy(), g.vals.copy()
+    for i in range(g.n):
+        b, e = g.rowptr[i], g.rowptr[i + 1]
+        o = rng.permutation(e - b)
+        col[b:e], val[b:e] = col[b:e][o], val[b:e][o]
+    p1, p2 = host_plan(g), ag.ag_plan_create(g.rowptr, col, val, g.n, 8, flags=ag.AG_FLAG_HOST_ONLY)
+    e1, e2 = ag.ag_plan_export(p1), ag.ag_plan_export(p2)
+    for k in e1:
+        assert np.array_equal(e1[k], e2[k]), k
+    ag.ag_plan_destroy(p1)
+    ag.ag_plan_destroy(p2)
+
+
+def expect_error(code, fn):
+    with pytest.raises(ag.AdaptGearError) as ei:
+        fn()
+    assert ei.value.code == code, ei.value
+
+
+def test_input_validation():
+    g = planted_partition(2, 16, 4, 0.7, 1)
+    rp, ci = g.rowptr.copy(), g.colidx.copy()
+    bad = ci.copy(); bad[3] = g.n
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, bad, None, g.n, 4, flags=1))
+    bad = ci.copy(); bad[0] = -1
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, bad, None, g.n, 4, flags=1))
+    bad = rp.copy(); bad[5] = bad[4] - 1
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(bad, ci, None, g.n, 4, flags=1))
+    dup = ci.copy(); dup[rp[1] - 1] = dup[rp[1] - 2] if rp[1] - rp[0] >= 2 else dup[0]
+    if rp[1] - rp[0] >= 2:
+        expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, dup, None, g.n, 4, flags=1))
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n + 1, 4, flags=1))
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 0, flags=1))
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 4, flags=1, block_cap=129))
+    p = host_plan(g)
+    expect_error(ag.AG_ERR_UNSUPPORTED, lambda: ag.ag_plan_force_kernels(p, ag.AG_CLS_BLOCKS_SPARSE, 0, 1))
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_force_kernels(p, 7, 0, 0))
+    ag.ag_plan_force_kernels(p, ag.AG_CLS_COMPOSE, ag.AG_DIR_FWD, ag.AG_COMPOSE_FUSED)
+    ag.ag_plan_destroy(p)
