@@ -325,11 +325,12 @@ void record_trial(ag_plan *p, Selector &s, const int *k, hipEvent_t *ev)
 
 int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
 {
-    if (!p || !X || !Y) { set_error("null argument"); return AG_ERR_INVALID; }
-    if (X == Y) { set_error("input and output must not alias"); return AG_ERR_INVALID; }
+    if (!p) { set_error("null plan"); return AG_ERR_INVALID; }
     Topology &t = *p->topo;
     if (t.host_only) { set_error("plan was created with AG_FLAG_HOST_ONLY"); return AG_ERR_UNSUPPORTED; }
     if (t.n == 0) return AG_OK;
+    if (!X || !Y) { set_error("null argument"); return AG_ERR_INVALID; }
+    if (X == Y) { set_error("input and output must not alias"); return AG_ERR_INVALID; }
     hipStream_t st = (hipStream_t)stream;
     const int dir_idx = (dir == AG_DIR_BWD && !t.symmetric) ? 1 : 0;
     Selector &s = p->sel[dir];
