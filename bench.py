@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the aggregation hot path on one MI355X.
+
+A step = one forward aggregation Y = A.H plus one backward aggregation dH = A^T.G on the
+workload's graph and feature width, through the C ABI (ag_aggregate / ag_aggregate_t) on
+plan-ordered features resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config IDX] [--no-cpu] [--no-gcn]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(st, F, compose, cls):
+    """Algorithmic HBM bytes of one launch of the kernel(s) of class `cls`.
+
+    Remainder: its CSR arrays once, one feature-row fetch per stored entry (the sources of the
+    inter-community subgraph have no locality by construction), one write of every output
+    row, plus the read of the block rows it accumulates onto.  Blocks: block topology once,
+    every feature row once, every output row once.
+    """
+    n, nbr = st["n"], st["n_block_rows"]
+    wbytes = 0 if st["unit_weights"] else 4
+    row = 4 * F
+    if cls == 2:
+        if compose == 2:                       # one CSR over everything
+            return 4 * (n + 1) + (4 + wbytes) * st["nnz"] + row * (n + st["nnz_inter"]) + row * n
+        if compose == 1:                       # tail rows only; block rows were fused
+            return 0
+        return 4 * (n + 1) + (4 + wbytes) * st["nnz_inter"] + row * st["nnz_inter"] + row * n + row * nbr
+    if compose == 1 and cls == 0:              # fused block kernel: intra + remainder of block rows
+        return (4 * (nbr + 1) + (1 + wbytes) * st["nnz_intra"] + 4 * (n + 1) + (4 + wbytes) * st["nnz_inter"]
+                + row * (nbr + st["nnz_inter"]) + row * n)
+    return 4 * (nbr + 1) + (1 + wbytes) * st["nnz_intra"] + 2 * row * nbr
+
+
+def measured_traffic(config, F, compose):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summaries, or None."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "hbm_traffic_bytes.txt")):
+            t = line.split()
+            if len(t) == 4 and not line.startswith("#") and (int(t[0]), int(t[1]), int(t[2])) == (config, F, compose):
+                return int(t[3])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (0-based)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-gcn", action="store_true", help="skip the GCN training-step timing")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the path is single-GPU by design); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2305_17408_amd as ag
+    from ag_inputs import config_graph, CONFIGS, features, glorot_uniform, labels
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    cfg = CONFIGS[args.config]
+    F = cfg["F"]
+    t0 = time.time()
+    g = config_graph(args.config)
+    log(f"[bench] graph {cfg['name']}: n={g.n} nnz={g.nnz} F={F} ({time.time() - t0:.1f}s)")
+    t0 = time.time()
+    plan = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, F, layout=ag.AG_LAYOUT_REORDERED)
+    t_plan = time.time() - t0
+    st = ag.ag_plan_stats(plan)
+    log(f"[bench] plan: {t_plan:.1f}s blocks={st['n_blocks']} dense={st['n_dense_blocks']} "
+        f"intra={st['nnz_intra']} inter={st['nnz_inter']} long_rows={st['n_long_rows']}")
+
+    H = torch.from_numpy(features(g.n, F, 7)).to(dev)
+    G = torch.from_numpy(features(g.n, F, 8)).to(dev)
+    Hp, Gp = torch.empty_like(H), torch.empty_like(G)
+    ag.ag_permute_rows(plan, H, Hp, F, False)
+    ag.ag_permute_rows(plan, G, Gp, F, False)
+    Y, dH = torch.empty_like(H), torch.empty_like(H)
+    torch.cuda.synchronize()
+
+    def step():
+        ag.ag_aggregate(plan, Hp, Y)
+        ag.ag_aggregate_t(plan, Gp, dH)
+
+    # selector trials belong to plan set-up ("first iterations"): run until both directions froze
+    sel_calls = 0
+    t0 = time.time()
+    while not (ag.ag_plan_selector_info(plan, 0)["frozen"] and ag.ag_plan_selector_info(plan, 1)["frozen"]):
+        step()
+        sel_calls += 1
+        if sel_calls > 200:
+            break
+    torch.cuda.synchronize()
+    t_sel = time.time() - t0
+    sel = [ag.ag_plan_selector_info(plan, d) for d in (0, 1)]
+    log(f"[bench] selector froze after {sel_calls} steps ({t_sel:.2f}s): fwd {sel[0]['choice']} bwd {sel[1]['choice']}")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt * 1e3 / args.steps
+    flop = 4.0 * g.nnz * F
+    gflops = flop / (ms_step * 1e-3) / 1e9
+    compulsory = 2 * (4 * (g.n + 1) + (4 + (0 if g.vals is None else 4)) * g.nnz + 8 * g.n * F)
+    log(f"[bench] {ms_step:.4f} ms/step  {gflops:.1f} GFLOP/s  effective {compulsory / ms_step / 1e6:.1f} GB/s")
+
+    # the same steps again with HIP events around every subgraph kernel (roofline figures)
+    ag.ag_plan_set_profiling(plan, True)
+    for _ in range(args.steps):
+        step()
+    prof = [ag.ag_plan_profile(plan, d) for d in (0, 1)]
+    ag.ag_plan_set_profiling(plan, False)
+    cls_names = {0: "dense-class blocks", 1: "sparse-class blocks", 2: "remainder CSR"}
+    per_class = {}
+    for c in range(3):
+        ms = sum(p["class_ms"][c] for p in prof)
+        calls = sum(p["calls"] for p in prof)
+        per_class[c] = ms / max(1, calls)
+    dom = max(per_class, key=per_class.get)
+    compose = prof[0]["compose"]
+    if compose == 1 and dom == 0:
+        dom_name = "k_block_sparse<fused> (intra blocks + their remainder rows)"
+    elif dom == 2:
+        dom_name = "k_csr_rows (+ long-row segments)"
+    else:
+        dom_name = "k_block_dense" if (dom == 0 and sel[0]["choice"][0] == 1) else "k_block_sparse"
+    abytes = algorithmic_bytes(st, F, compose, dom)
+    achieved = abytes / (per_class[dom] * 1e-3) / 1e9 if per_class[dom] > 0 else 0.0
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": measured_traffic(args.config, F, compose) if dom == 2 else None,
+                "kernel": dom_name, "class": cls_names[dom], "avg_launch_ms": round(per_class[dom], 5),
+                "algorithmic_bytes_per_launch": int(abytes),
+                "per_class_ms": {cls_names[c]: round(per_class[c], 5) for c in per_class}}
+    log(f"[bench] roofline: {roofline}")
+
+    out = {
+        "metric": "aggregation GFLOP/s (fwd+bwd SpMM, fp32)", "value": round(gflops, 2), "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {cfg['name']}: N={g.n}, nnz={g.nnz}, F={F}, "
+                               "one forward + one backward aggregation, plan-ordered features",
+                   "n": g.n, "nnz": g.nnz, "F": F, "layout": "reordered"},
+        "effective_hbm_gbs": round(compulsory / ms_step / 1e6, 1),
+        "compulsory_bytes_per_step": int(compulsory),
+        "plan_create_s": round(t_plan, 2), "selector_steps": sel_calls, "selector_s": round(t_sel, 3),
+        "selector_choice": {"fwd": sel[0]["choice"], "bwd": sel[1]["choice"]},
+        "plan": {k: st[k] for k in ("n_blocks", "n_block_rows", "n_dense_blocks", "nnz_intra", "nnz_inter",
+                                    "n_long_rows", "sec_reorder", "sec_split", "sec_build", "sec_upload",
+                                    "device_bytes")},
+        "roofline": roofline,
+    }
+
+    # ms per 2-layer GCN training step (only defined for the GCN workload)
+    if not args.no_gcn and "hidden" in cfg:
+        hid, ncls = cfg["hidden"], cfg["classes"]
+        p_out = ag.ag_plan_clone_for_width(plan, ncls)
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        W1, W2 = t(glorot_uniform(F, hid, 21)), t(glorot_uniform(hid, ncls, 22))
+        b1, b2 = torch.zeros(hid, device=dev), torch.zeros(ncls, device=dev)
+        perm = ag.ag_plan_export(plan)["perm"]
+        yl = t(labels(g.n, ncls, 23)[perm])
+        dW1, db1 = torch.empty_like(W1), torch.empty_like(b1)
+        dW2, db2 = torch.empty_like(W2), torch.empty_like(b2)
+        loss = torch.empty(1, device=dev)
+        ws = torch.empty(ag.ag_gcn_workspace_bytes(g.n, F, hid, ncls) // 4, device=dev)
+
+        def gcn():
+            ag.ag_gcn_step(plan, p_out, f_in=F, hidden=hid, n_class=ncls, W1=W1, b1=b1, W2=W2, b2=b2,
+                           dW1=dW1, db1=db1, dW2=dW2, db2=db2, loss=loss, logits=None, X=Hp, labels=yl,
+                           workspace=ws)
+        n_sel = 0
+        while n_sel < 60 and not (ag.ag_plan_selector_info(p_out, 0)["frozen"]
+                                  and ag.ag_plan_selector_info(p_out, 1)["frozen"]):
+            gcn()
+            n_sel += 1
+        for _ in range(3):
+            gcn()
+        torch.cuda.synchronize()
+        k = max(5, args.steps // 5)
+        t0 = time.perf_counter()
+        for _ in range(k):
+            gcn()
+        torch.cuda.synchronize()
+        out["gcn_step_ms"] = round((time.perf_counter() - t0) * 1e3 / k, 4)
+        out["gcn_loss"] = round(float(loss.item()), 6)
+        log(f"[bench] GCN step {out['gcn_step_ms']} ms, loss {out['gcn_loss']}")
+        ag.ag_plan_destroy(p_out)
+
+    if not args.no_cpu:
+        import oracle
+        Hh, Gh = H.cpu().numpy(), G.cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.spmm(g.rowptr, g.colidx, g.vals, Hh, want_abs=False, threads=True)
+        oracle.spmm_t(g.rowptr, g.colidx, g.vals, Gh, want_abs=False, threads=True)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(flop / cpu_s / 1e9, 3), "unit": "GFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"one full step (1 forward + 1 backward aggregation) of the same workload, "
+                                         f"{cpu_s:.2f} s, fp64, OpenMP"}
+        log(f"[bench] cpu oracle: {cpu_s:.2f}s")
+    ag.ag_plan_destroy(plan)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

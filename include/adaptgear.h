@@ -141,6 +141,23 @@ typedef struct {
 
 int ag_plan_selector_info(const ag_plan *p, int32_t dir, ag_selector_info *out);
 
+/* Per-kernel timing of ordinary (non-trial) calls, the "monitor" of Sec. 3.3 kept available
+ * after the trials: while switched on, every call records HIP events on the caller's stream
+ * around its subgraph kernels.  ag_plan_profile waits for the recorded events and returns the
+ * sums since profiling was switched on.  With AG_COMPOSE_SPLIT class_ms[0..2] are the dense-
+ * class block kernel, the sparse-class block kernel and the remainder kernels; with
+ * AG_COMPOSE_FUSED class_ms[0] is the fused block kernel and class_ms[2] the tail/long-row
+ * kernels; with AG_COMPOSE_FULL_CSR everything is in class_ms[2]. */
+typedef struct {
+    int64_t calls;
+    double  class_ms[3];
+    double  total_ms;
+    int32_t compose;
+} ag_profile;
+
+int ag_plan_set_profiling(ag_plan *p, int32_t on);
+int ag_plan_profile(ag_plan *p, int32_t dir, ag_profile *out);
+
 /* ---- inspection (tests, reports) -------------------------------------------------------- */
 
 /* Host views of the decomposition, owned by the plan, valid until it is destroyed.

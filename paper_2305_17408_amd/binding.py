@@ -66,6 +66,11 @@ class ag_stats(C.Structure):
                 ("sec_upload", C.c_double), ("device_bytes", C.c_int64)]
 
 
+class ag_profile(C.Structure):
+    _fields_ = [("calls", C.c_int64), ("class_ms", C.c_double * 3), ("total_ms", C.c_double),
+                ("compose", C.c_int32)]
+
+
 class ag_gcn_io(C.Structure):
     _fields_ = [("f_in", C.c_int32), ("hidden", C.c_int32), ("n_class", C.c_int32),
                 ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
@@ -75,7 +80,7 @@ class ag_gcn_io(C.Structure):
 
 EXPORTS = ["ag_plan_create", "ag_plan_clone_for_width", "ag_plan_destroy", "ag_aggregate",
            "ag_aggregate_t", "ag_permute_rows", "ag_plan_force_kernels", "ag_plan_selector_info",
-           "ag_plan_export", "ag_plan_stats", "ag_last_error", "ag_gin_layer", "ag_gin_layer_t",
+           "ag_plan_export", "ag_plan_stats", "ag_plan_set_profiling", "ag_plan_profile", "ag_last_error", "ag_gin_layer", "ag_gin_layer_t",
            "ag_gcn_workspace_bytes", "ag_gcn_step"]
 
 _lib = None
@@ -101,6 +106,8 @@ def lib() -> C.CDLL:
         L.ag_plan_selector_info.argtypes = [vp, C.c_int32, C.POINTER(ag_selector_info)]
         L.ag_plan_export.argtypes = [vp, C.POINTER(ag_export)]
         L.ag_plan_stats.argtypes = [vp, C.POINTER(ag_stats)]
+        L.ag_plan_set_profiling.argtypes = [vp, C.c_int32]
+        L.ag_plan_profile.argtypes = [vp, C.c_int32, C.POINTER(ag_profile)]
         L.ag_last_error.restype = C.c_char_p
         L.ag_gin_layer.argtypes = [vp, C.c_float, vp, vp, vp]
         L.ag_gin_layer_t.argtypes = [vp, C.c_float, vp, vp, vp]
@@ -222,6 +229,17 @@ def ag_plan_stats(plan) -> dict:
     s = ag_stats()
     _check(lib().ag_plan_stats(plan, C.byref(s)))
     return {k: getattr(s, k) for k, _ in ag_stats._fields_}
+
+
+def ag_plan_set_profiling(plan, on: bool) -> None:
+    _check(lib().ag_plan_set_profiling(plan, 1 if on else 0))
+
+
+def ag_plan_profile(plan, direction: int) -> dict:
+    s = ag_profile()
+    _check(lib().ag_plan_profile(plan, int(direction), C.byref(s)))
+    return dict(calls=int(s.calls), class_ms=list(s.class_ms), total_ms=float(s.total_ms),
+                compose=int(s.compose))
 
 
 def ag_gin_layer(plan, eps: float, H, Y, stream=None) -> None:

@@ -159,10 +159,19 @@ struct ag_plan {
     Selector sel[2];
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     std::vector<void *> owned;
+    // optional per-call kernel timing (ag_plan_set_profiling): a ring of event quadruples
+    struct Pending { int dir; int slot; };
+    bool profiling = false;
+    std::vector<hipEvent_t> prof_ev;            // 4 * kProfRing events
+    std::vector<Pending> prof_pending;
+    int prof_next = 0;
+    double prof_ms[2][3] = {{0, 0, 0}, {0, 0, 0}}, prof_total[2] = {0, 0};
+    int64_t prof_calls[2] = {0, 0};
 
     ~ag_plan()
     {
         for (auto &e : ev) if (e) (void)hipEventDestroy(e);
+        for (auto &e : prof_ev) if (e) (void)hipEventDestroy(e);
         if (topo) for (void *p : owned) topo->opt.dev_free(p, topo->opt.user);
     }
 };
@@ -323,6 +332,28 @@ void record_trial(ag_plan *p, Selector &s, const int *k, hipEvent_t *ev)
     if (++s.rep > p->trials) { s.rep = 0; ++s.cand; }
 }
 
+constexpr int kProfRing = 64;
+
+void prof_drain(ag_plan *p)
+{
+    for (const auto &q : p->prof_pending) {
+        hipEvent_t *e = p->prof_ev.data() + 4 * q.slot;
+        float a = 0, b = 0, c = 0, d = 0;
+        (void)hipEventSynchronize(e[3]);
+        (void)hipEventElapsedTime(&a, e[0], e[1]);
+        (void)hipEventElapsedTime(&b, e[1], e[2]);
+        (void)hipEventElapsedTime(&c, e[2], e[3]);
+        (void)hipEventElapsedTime(&d, e[0], e[3]);
+        p->prof_ms[q.dir][0] += a;
+        p->prof_ms[q.dir][1] += b;
+        p->prof_ms[q.dir][2] += c;
+        p->prof_total[q.dir] += d;
+        p->prof_calls[q.dir]++;
+    }
+    p->prof_pending.clear();
+    p->prof_next = 0;
+}
+
 int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
 {
     if (!p) { set_error("null plan"); return AG_ERR_INVALID; }
@@ -348,7 +379,13 @@ int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
     if (trial && !p->ev[0])
         for (auto &e : p->ev)
             if ((rc = hip_fail((int)hipEventCreate(&e), "event create"))) return rc;
-    if ((rc = run_choice(p, dir_idx, k, in, out, st, trial ? p->ev : nullptr))) return rc;
+    hipEvent_t *evs = trial ? p->ev : nullptr;
+    if (!trial && p->profiling) {
+        if ((int)p->prof_pending.size() >= kProfRing) prof_drain(p);
+        evs = p->prof_ev.data() + 4 * p->prof_next;
+        p->prof_pending.push_back({dir, p->prof_next++});
+    }
+    if ((rc = run_choice(p, dir_idx, k, in, out, st, evs))) return rc;
     if (trial) record_trial(p, s, k, p->ev);
     if (p->layout == AG_LAYOUT_ORIGINAL)
         if ((rc = launch_permute_rows(t.perm_dev, t.n, p->F, p->tmp_out, Y, true, st))) return rc;
@@ -521,6 +558,38 @@ int ag_plan_selector_info(const ag_plan *p, int32_t dir, ag_selector_info *out)
         for (int k = 0; k < 4; ++k) out->trial_ms[c][k] = s.median_ms[c][k];
     }
     out->total_trial_ms = s.total_trial_ms;
+    return AG_OK;
+}
+
+int ag_plan_set_profiling(ag_plan *p, int32_t on)
+{
+    if (!p) { set_error("null plan"); return AG_ERR_INVALID; }
+    if (p->topo->host_only) { set_error("host-only plan"); return AG_ERR_UNSUPPORTED; }
+    prof_drain(p);
+    for (int d = 0; d < 2; ++d) {
+        p->prof_total[d] = 0;
+        p->prof_calls[d] = 0;
+        for (int c = 0; c < 3; ++c) p->prof_ms[d][c] = 0;
+    }
+    if (on && p->prof_ev.empty()) {
+        p->prof_ev.assign(4 * kProfRing, nullptr);
+        for (auto &e : p->prof_ev) {
+            int rc = hip_fail((int)hipEventCreate(&e), "event create");
+            if (rc) return rc;
+        }
+    }
+    p->profiling = on != 0;
+    return AG_OK;
+}
+
+int ag_plan_profile(ag_plan *p, int32_t dir, ag_profile *out)
+{
+    if (!p || !out || (dir != AG_DIR_FWD && dir != AG_DIR_BWD)) { set_error("bad argument"); return AG_ERR_INVALID; }
+    prof_drain(p);
+    out->calls = p->prof_calls[dir];
+    for (int c = 0; c < 3; ++c) out->class_ms[c] = p->prof_ms[dir][c];
+    out->total_ms = p->prof_total[dir];
+    out->compose = p->sel[dir].choice[AG_CLS_COMPOSE];
     return AG_OK;
 }
 

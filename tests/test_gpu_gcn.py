@@ -1,0 +1,74 @@
+"""GPU parity of the two-layer GCN training step against the fp64 oracle."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2305_17408_amd as ag
+from ag_inputs import config_graph, planted_partition, row_normalise, features, glorot_uniform, labels
+from gpu_util import say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_step(g, fin, hid, ncls, seed=0, zero=False):
+    import torch
+    dev = "cuda"
+    plan_in = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, fin, layout=ag.AG_LAYOUT_REORDERED)
+    plan_out = ag.ag_plan_clone_for_width(plan_in, ncls)
+    perm = ag.ag_plan_export(plan_in)["perm"]
+    X = features(g.n, fin, 10 + seed)
+    W1 = glorot_uniform(fin, hid, 11 + seed)
+    W2 = glorot_uniform(hid, ncls, 12 + seed)
+    b1 = (0.05 * features(1, hid, 13 + seed)[0]).astype(np.float32)
+    b2 = (0.05 * features(1, ncls, 14 + seed)[0]).astype(np.float32)
+    if zero:
+        W1, W2, b1, b2 = W1 * 0, W2 * 0, b1 * 0, b2 * 0
+    y = labels(g.n, ncls, 15 + seed)
+    ref = oracle.gcn_step(g.rowptr, g.colidx, g.vals, X, W1, b1, W2, b2, y)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    Xp, yp = t(X[perm]), t(y[perm])                      # plan order
+    dW1, db1 = torch.empty(fin, hid, device=dev), torch.empty(hid, device=dev)
+    dW2, db2 = torch.empty(hid, ncls, device=dev), torch.empty(ncls, device=dev)
+    loss = torch.empty(1, device=dev)
+    logits = torch.empty(g.n, ncls, device=dev)
+    ws = torch.empty(ag.ag_gcn_workspace_bytes(g.n, fin, hid, ncls) // 4, device=dev)
+    for rep in range(2):
+        ag.ag_gcn_step(plan_in, plan_out, f_in=fin, hidden=hid, n_class=ncls, W1=t(W1), b1=t(b1), W2=t(W2),
+                       b2=t(b2), dW1=dW1, db1=db1, dW2=dW2, db2=db2, loss=loss, logits=logits, X=Xp,
+                       labels=yp, workspace=ws)
+    torch.cuda.synchronize()
+    ag.ag_plan_destroy(plan_out)
+    ag.ag_plan_destroy(plan_in)
+    got = dict(loss=float(loss.item()), dW1=dW1.cpu().numpy(), db1=db1.cpu().numpy(),
+               dW2=dW2.cpu().numpy(), db2=db2.cpu().numpy(), Z=logits.cpu().numpy())
+    return got, ref, perm
+
+
+def compare(got, ref, perm):
+    assert abs(got["loss"] - ref.loss) <= 1e-5 * abs(ref.loss), (got["loss"], ref.loss)
+    np.testing.assert_allclose(got["Z"], ref.Z[perm], rtol=0, atol=1e-4 * np.abs(ref.Z).max())
+    for k in ("dW1", "db1", "dW2", "db2"):
+        r = getattr(ref, k)
+        err = np.abs(got[k] - r).max()
+        assert err <= 1e-4 * np.abs(r).max(), (k, err, np.abs(r).max())
+
+
+def test_gcn_step_small_nonsymmetric():
+    g = row_normalise(planted_partition(16, 64, 8, 0.7, 5))      # a missing transpose would show
+    got, ref, perm = run_step(g, 24, 40, 8)
+    compare(got, ref, perm)
+
+
+def test_gcn_step_config3_shape_scaled():
+    g = config_graph(3, scale=1 / 64)
+    got, ref, perm = run_step(g, 128, 256, 16)
+    say("loss", got["loss"], ref.loss)
+    compare(got, ref, perm)
+
+
+def test_gcn_zero_weights_loss_is_log16():
+    g = config_graph(3, scale=1 / 256)
+    got, ref, perm = run_step(g, 128, 256, 16, zero=True)
+    assert abs(got["loss"] - math.log(16.0)) < 1e-5
