@@ -119,6 +119,10 @@ int launch_relu_grad(int64_t count, const float *act, float *grad, void *stream)
 size_t col_sum_scratch_floats(int32_t f);
 int launch_col_sum(int64_t n, int32_t f, const float *M, float *out, float *scratch, void *stream);
 int launch_fill_zero(int64_t count, float *p, void *stream);
+// kernels_gemm.hip
+size_t gemm_tn_scratch_floats(int32_t m, int32_t n);
+int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float *B, float *C,
+                   float *scratch, void *stream);
 
 void set_error(const std::string &msg);
 int  hip_fail(int hip_error_code, const char *what);

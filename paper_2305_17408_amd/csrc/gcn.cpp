@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <rocblas/rocblas.h>
 
+#include <algorithm>
 #include <mutex>
 
 #include "ag_internal.h"
@@ -73,7 +74,8 @@ struct Ws {
 size_t ws_floats(int64_t n, int32_t fi, int32_t hd, int32_t c)
 {
     return (size_t)n * ((size_t)fi + 2 * (size_t)hd + 4 * (size_t)c + 1) +
-           col_sum_scratch_floats(std::max(hd, c)) + 64;
+           std::max(col_sum_scratch_floats(std::max(hd, c)),
+                    std::max(gemm_tn_scratch_floats(fi, hd), gemm_tn_scratch_floats(hd, c))) + 64;
 }
 
 }  // namespace
@@ -135,10 +137,10 @@ int ag_gcn_step(ag_plan *p_in, ag_plan *p_out, const ag_gcn_io *io, const float 
     // backward
     if ((rc = launch_col_sum(n, c, w.dZ, io->db2, w.scratch, stream))) return rc;
     if ((rc = ag_aggregate_t(p_out, w.dZ, w.dQ, stream))) return rc;                // dQ = A^T dZ
-    if ((rc = gemm_rm(b, true, false, hd, c, n, w.H1, w.dQ, io->dW2))) return rc;   // dW2 = H1^T dQ
+    if ((rc = launch_gemm_tn(n, hd, c, w.H1, w.dQ, io->dW2, w.scratch, stream))) return rc;   // dW2 = H1^T dQ
     if ((rc = gemm_rm(b, false, true, n, hd, c, w.dQ, io->W2, w.dH1))) return rc;   // dH1 = dQ W2^T
     if ((rc = launch_relu_grad(n * (int64_t)hd, w.H1, w.dH1, stream))) return rc;   // through the ReLU
-    if ((rc = gemm_rm(b, true, false, fi, hd, n, w.P, w.dH1, io->dW1))) return rc;  // dW1 = P^T dPre
+    if ((rc = launch_gemm_tn(n, fi, hd, w.P, w.dH1, io->dW1, w.scratch, stream))) return rc;  // dW1 = P^T dPre
     if ((rc = launch_col_sum(n, hd, w.dH1, io->db1, w.scratch, stream))) return rc;
     return AG_OK;
 }
