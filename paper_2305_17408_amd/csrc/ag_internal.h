@@ -122,7 +122,10 @@ int launch_fill_zero(int64_t count, float *p, void *stream);
 // kernels_gemm.hip
 size_t gemm_tn_scratch_floats(int32_t m, int32_t n);
 int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float *B, float *C,
-                   float *scratch, void *stream);
+                   float *colsum, float *scratch, void *stream);
+int launch_gemm_nn(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
+                   const float *aux, void *stream);
+int launch_transpose_small(int32_t rows, int32_t cols, const float *in, float *out, void *stream);
 
 void set_error(const std::string &msg);
 int  hip_fail(int hip_error_code, const char *what);

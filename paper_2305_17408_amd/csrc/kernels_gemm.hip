@@ -4,7 +4,11 @@
 //           (the weight gradients dW = X^T dY).  K is split across work-groups; each writes a
 //           partial m x n tile and a second kernel adds the partials in a fixed order.
 //           Both MFMA operands are rows of A and B, so they are read coalesced and staged in LDS
-//           without any transposition.
+//           without any transposition.  Optionally the column sums of B (the bias gradient)
+//           are accumulated on the way from the values each thread loads anyway.
+// gemm_nn:  C[N x n] = epilogue(A[N x k] W[k x n]) with N = number of vertices: the layer
+//           transforms.  Epilogues: none, + bias then ReLU, or masking by a ReLU activation
+//           (the backward through the ReLU), fused so the N x n result is written once.
 #include "kernels_common.h"
 
 namespace ag {
@@ -34,7 +38,7 @@ __device__ __forceinline__ float4 guarded_load4(const float *__restrict__ M, int
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, const float *__restrict__ B,
                                                  float *__restrict__ part, int64_t K, int m, int n,
-                                                 int64_t rows_per_chunk)
+                                                 int64_t rows_per_chunk, float *__restrict__ colsum_part)
 {
     constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
     constexpr int NA = kKS * TM / 4, NB = kKS * TN / 4;                 // float4 units per stage
@@ -56,7 +60,10 @@ __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, co
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    float4 ra[UA], rb[UB];
+    float4 ra[UA], rb[UB], cs[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) cs[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const bool want_cs = colsum_part != nullptr && blockIdx.y == 0;
     auto fetch = [&](int64_t k0) {
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
@@ -66,7 +73,10 @@ __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, co
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
             const int idx = tid + u * kWG, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
-            if (idx < NB) rb[u] = guarded_load4(B, k0 + r, k_end, n0 + c, n, vb);
+            if (idx < NB) {
+                rb[u] = guarded_load4(B, k0 + r, k_end, n0 + c, n, vb);
+                cs[u].x += rb[u].x; cs[u].y += rb[u].y; cs[u].z += rb[u].z; cs[u].w += rb[u].w;
+            }
         }
     };
     auto stash = [&](int buf) {
@@ -108,6 +118,22 @@ __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, co
         __syncthreads();
         buf ^= 1;
     }
+    if (want_cs) {
+        // threads that loaded the same columns (different staged rows) are combined through LDS
+        float *red = &sB[0][0][0];                    // kKS x TN floats, free after the last barrier
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int idx = tid + u * kWG, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
+            if (idx < NB) *reinterpret_cast<float4 *>(&red[r * TN + c]) = cs[u];
+        }
+        __syncthreads();
+        for (int c = tid; c < TN; c += kWG) {
+            float t = 0.f;
+#pragma unroll
+            for (int r = 0; r < kKS; ++r) t += red[r * TN + c];
+            if (n0 + c < n) colsum_part[(size_t)blockIdx.x * n + n0 + c] = t;
+        }
+    }
     float *out = part + (size_t)blockIdx.x * m * n;
 #pragma unroll
     for (int i = 0; i < WM; ++i)
@@ -133,32 +159,244 @@ __global__ __launch_bounds__(kWG) void k_sum_partials(int nchunks, int64_t count
     C[i] = s;
 }
 
+
+// ------------------------------------------------------------------------------------------
+// C[N x n] = epilogue(A[N x k] W[k x n])
+// ------------------------------------------------------------------------------------------
+enum { EPI_NONE = 0, EPI_BIAS_RELU = 1, EPI_RELU_MASK = 2 };
+constexpr int kNK = 16;             // k columns of A / rows of W staged per step
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
+__global__ __launch_bounds__(kWG, 2) void k_gemm_nn(const float *__restrict__ A, const float *__restrict__ W,
+                                                 float *__restrict__ C, int64_t N, int k, int n,
+                                                 const float *__restrict__ aux)
+{
+    constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
+    constexpr int LDA = kNK + 1;                                        // padded: conflict-free operand reads
+    constexpr int NA = TM * kNK / 4, NW = kNK * TN / 4;
+    constexpr int UA = (NA + kWG - 1) / kWG, UW = (NW + kWG - 1) / kWG;
+    __shared__ float sA[TM * LDA];
+    __shared__ float sW[kNK][TN];
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    const int wm = w / WAVES_N, wn = w % WAVES_N;
+    const int64_t r0 = (int64_t)blockIdx.x * TM;
+    const int n0 = blockIdx.y * TN;
+    const bool va = (k % 4 == 0), vw = (n % 4 == 0);
+
+    floatx16 acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    float4 ra[UA], rw[UW];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * kWG, r = idx / (kNK / 4), c = (idx % (kNK / 4)) * 4;
+            if (idx < NA) ra[u] = guarded_load4(A, r0 + r, N, k0 + c, k, va);
+        }
+#pragma unroll
+        for (int u = 0; u < UW; ++u) {
+            const int idx = tid + u * kWG, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
+            if (idx < NW) rw[u] = guarded_load4(W, k0 + r, k, n0 + c, n, vw);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * kWG, r = idx / (kNK / 4), c = (idx % (kNK / 4)) * 4;
+            if (idx < NA) {
+                float *d = &sA[r * LDA + c];
+                d[0] = ra[u].x; d[1] = ra[u].y; d[2] = ra[u].z; d[3] = ra[u].w;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UW; ++u) {
+            const int idx = tid + u * kWG, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
+            if (idx < NW) *reinterpret_cast<float4 *>(&sW[r][c]) = rw[u];
+        }
+    };
+
+    fetch(0);
+    for (int k0 = 0; k0 < k; k0 += kNK) {
+        __syncthreads();                       // everyone is done reading the previous tiles
+        stash();
+        __syncthreads();
+        if (k0 + kNK < k) fetch(k0 + kNK);
+#pragma unroll
+        for (int s = 0; s < kNK / 2; ++s) {
+            float a[WM], b[WN];
+#pragma unroll
+            for (int i = 0; i < WM; ++i) a[i] = sA[((wm * WM + i) * 32 + lo) * LDA + 2 * s + hi];
+#pragma unroll
+            for (int j = 0; j < WN; ++j) b[j] = sW[2 * s + hi][(wn * WN + j) * 32 + lo];
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int col = n0 + (wn * WN + j) * 32 + lo;
+            if (col >= n) continue;
+            float bias = 0.f;
+            if constexpr (EPI == EPI_BIAS_RELU) bias = aux[col];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = r0 + (wm * WM + i) * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
+                if (row >= N) continue;
+                float v = acc[i][j][r];
+                if constexpr (EPI == EPI_BIAS_RELU) v = fmaxf(v + bias, 0.f);
+                if constexpr (EPI == EPI_RELU_MASK) v = (aux[row * n + col] > 0.f) ? v : 0.f;
+                C[row * n + col] = v;
+            }
+        }
+}
+
+// out[c][r] = in[r][c] for a small rows x cols matrix
+__global__ __launch_bounds__(kWG) void k_transpose_small(int rows, int cols, const float *__restrict__ in,
+                                                         float *__restrict__ out)
+{
+    const int i = blockIdx.x * kWG + threadIdx.x;
+    if (i >= rows * cols) return;
+    const int r = i / cols, c = i % cols;
+    out[(size_t)c * rows + r] = in[i];
+}
+
+// Small inner dimension (k <= KMAX): a bandwidth-bound outer-product update on the vector ALUs.
+// A thread owns 4 consecutive output columns; its slice of W lives in registers and is reused
+// for ROWS consecutive rows per work-group pass.
+template <int KMAX, int EPI>
+__global__ __launch_bounds__(kWG) void k_gemm_nn_smallk(const float *__restrict__ A, const float *__restrict__ W,
+                                                        float *__restrict__ C, int64_t N, int k, int n,
+                                                        const float *__restrict__ aux, int rows_per_wg)
+{
+    const int tpr = (n + 3) / 4;                         // threads per row, <= kWG
+    const int rows_at_once = kWG / tpr;
+    const int sub = threadIdx.x / tpr, c = (threadIdx.x % tpr) * 4;
+    if (sub >= rows_at_once) return;
+    float4 wreg[KMAX];
+#pragma unroll
+    for (int q = 0; q < KMAX; ++q) wreg[q] = guarded_load4(W, q, k, c, n, (n % 4) == 0);
+    float4 bias = make_float4(0.f, 0.f, 0.f, 0.f);
+    if constexpr (EPI == EPI_BIAS_RELU) bias = guarded_load4(aux, 0, 1, c, n, (n % 4) == 0);
+    const int64_t rb = (int64_t)blockIdx.x * rows_per_wg;
+    const int64_t re = min(N, rb + rows_per_wg);
+    const bool vec = (n % 4 == 0), va = (k % 4 == 0);
+    for (int64_t row = rb + sub; row < re; row += rows_at_once) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int q4 = 0; q4 < KMAX; q4 += 4) {
+            const float4 a = guarded_load4(A, row, N, q4, k, va);
+            const float av[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (q4 + j < KMAX) {
+                    acc.x = fmaf(av[j], wreg[q4 + j].x, acc.x);
+                    acc.y = fmaf(av[j], wreg[q4 + j].y, acc.y);
+                    acc.z = fmaf(av[j], wreg[q4 + j].z, acc.z);
+                    acc.w = fmaf(av[j], wreg[q4 + j].w, acc.w);
+                }
+            }
+        }
+        if constexpr (EPI == EPI_BIAS_RELU) {
+            acc.x = fmaxf(acc.x + bias.x, 0.f); acc.y = fmaxf(acc.y + bias.y, 0.f);
+            acc.z = fmaxf(acc.z + bias.z, 0.f); acc.w = fmaxf(acc.w + bias.w, 0.f);
+        }
+        if constexpr (EPI == EPI_RELU_MASK) {
+            const float4 mk = guarded_load4(aux, row, N, c, n, vec);
+            acc.x = mk.x > 0.f ? acc.x : 0.f; acc.y = mk.y > 0.f ? acc.y : 0.f;
+            acc.z = mk.z > 0.f ? acc.z : 0.f; acc.w = mk.w > 0.f ? acc.w : 0.f;
+        }
+        float *o = C + row * n + c;
+        if (vec && c + 3 < n) {
+            *reinterpret_cast<float4 *>(o) = acc;
+        } else {
+            const float ov[4] = {acc.x, acc.y, acc.z, acc.w};
+            for (int j = 0; j < 4 && c + j < n; ++j) o[j] = ov[j];
+        }
+    }
+}
+
+template <int EPI>
+void run_nn(int64_t N, int k, int n, const float *A, const float *W, float *C, const float *aux, hipStream_t st)
+{
+    if (k <= 16 && n <= 4 * kWG) {
+        const int rows_per_wg = 64;
+        hipLaunchKernelGGL((k_gemm_nn_smallk<16, EPI>), dim3((unsigned)((N + rows_per_wg - 1) / rows_per_wg)),
+                           dim3(kWG), 0, st, A, W, C, N, k, n, aux, rows_per_wg);
+        return;
+    }
+    if (n > 32) {
+        dim3 grid((unsigned)((N + 127) / 128), (n + 255) / 256);
+        hipLaunchKernelGGL((k_gemm_nn<2, 2, 2, 4, EPI>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
+    } else {
+        dim3 grid((unsigned)((N + 127) / 128), 1);
+        hipLaunchKernelGGL((k_gemm_nn<4, 1, 1, 1, EPI>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
+    }
+}
+
 }  // namespace
 
-size_t gemm_tn_scratch_floats(int32_t m, int32_t n) { return (size_t)kMaxChunks * m * n; }
+size_t gemm_tn_scratch_floats(int32_t m, int32_t n) { return (size_t)kMaxChunks * ((size_t)m + 1) * n; }
 
 // C[m x n] = A^T B, A [K x m], B [K x n]; scratch holds gemm_tn_scratch_floats(m, n) floats.
+// colsum (optional, n floats) receives the column sums of B.
 int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float *B, float *C,
-                   float *scratch, void *stream)
+                   float *colsum, float *scratch, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     if (m <= 0 || n <= 0) return AG_OK;
-    if (K <= 0) return launch_fill_zero((int64_t)m * n, C, stream);
+    if (K <= 0) {
+        if (colsum) { int rc = launch_fill_zero(n, colsum, stream); if (rc) return rc; }
+        return launch_fill_zero((int64_t)m * n, C, stream);
+    }
+    float *cs_part = colsum ? scratch + (size_t)kMaxChunks * m * n : nullptr;
     int64_t steps = (K + kKS - 1) / kKS;
     int nchunks = (int)std::max<int64_t>(1, std::min<int64_t>(kMaxChunks, steps));
     int64_t rows_per_chunk = ((steps + nchunks - 1) / nchunks) * kKS;
     nchunks = (int)std::max<int64_t>(1, (K + rows_per_chunk - 1) / rows_per_chunk);
     if (n > 32) {
         dim3 grid(nchunks, (m + 127) / 128, (n + 255) / 256);
-        hipLaunchKernelGGL((k_gemm_tn<2, 2, 2, 4>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk);
+        hipLaunchKernelGGL((k_gemm_tn<2, 2, 2, 4>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     } else {
         dim3 grid(nchunks, (m + 255) / 256, 1);
-        hipLaunchKernelGGL((k_gemm_tn<4, 1, 2, 1>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk);
+        hipLaunchKernelGGL((k_gemm_tn<4, 1, 2, 1>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     }
     const int64_t count = (int64_t)m * n;
     hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + kWG - 1) / kWG)), dim3(kWG), 0, st, nchunks,
                        count, scratch, C);
+    if (colsum)
+        hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + kWG - 1) / kWG)), dim3(kWG), 0, st, nchunks,
+                           (int64_t)n, cs_part, colsum);
     return hip_fail((int)hipGetLastError(), "gemm_tn launch");
+}
+
+// C[N x n] = A[N x k] W[k x n]; epilogue 0: none, 1: relu(. + aux[n]), 2: masked by aux[N x n] > 0
+int launch_gemm_nn(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
+                   const float *aux, void *stream)
+{
+    if (N <= 0 || n <= 0) return AG_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (epilogue == EPI_BIAS_RELU) run_nn<EPI_BIAS_RELU>(N, k, n, A, W, C, aux, st);
+    else if (epilogue == EPI_RELU_MASK) run_nn<EPI_RELU_MASK>(N, k, n, A, W, C, aux, st);
+    else run_nn<EPI_NONE>(N, k, n, A, W, C, aux, st);
+    return hip_fail((int)hipGetLastError(), "gemm_nn launch");
+}
+
+int launch_transpose_small(int32_t rows, int32_t cols, const float *in, float *out, void *stream)
+{
+    if (rows <= 0 || cols <= 0) return AG_OK;
+    hipLaunchKernelGGL(k_transpose_small, dim3((rows * cols + kWG - 1) / kWG), dim3(kWG), 0, (hipStream_t)stream,
+                       rows, cols, in, out);
+    return hip_fail((int)hipGetLastError(), "transpose launch");
 }
 
 }  // namespace ag

@@ -112,15 +112,24 @@ __global__ __launch_bounds__(kWG) void k_col_sum_stage1(int64_t n, int f, int64_
     }
 }
 
-// stage 2: out[c] = sum_q part[q][c], fixed order
+// stage 2: out[c] = sum_q part[q][c]; 32 columns per work-group, 8 slices of the partial rows
+// per column, combined through LDS in a fixed order
 __global__ __launch_bounds__(kWG) void k_col_sum_stage2(int nq, int f, const float *__restrict__ part,
                                                         float *__restrict__ out)
 {
-    const int c = blockIdx.x * kWG + threadIdx.x;
-    if (c >= f) return;
+    __shared__ float red[kWG];
+    const int c = blockIdx.x * 32 + (threadIdx.x & 31), slice = threadIdx.x >> 5;
     float s = 0.f;
-    for (int q = 0; q < nq; ++q) s += part[(size_t)q * f + c];
-    out[c] = s;
+    if (c < f)
+        for (int q = slice; q < nq; q += 8) s += part[(size_t)q * f + c];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x < 32 && c < f) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t += red[k * 32 + threadIdx.x];
+        out[c] = t;
+    }
 }
 
 inline dim3 grid1(int64_t count) { return dim3((unsigned)((count + kWG - 1) / kWG)); }
@@ -187,7 +196,7 @@ int launch_col_sum(int64_t n, int32_t f, const float *M, float *out, float *scra
     if (n == 0) { nq = 0; }
     if (nq > 0)
         hipLaunchKernelGGL(k_col_sum_stage1, dim3(nq), dim3(kWG), 0, st, n, f, rows_per, M, scratch);
-    hipLaunchKernelGGL(k_col_sum_stage2, dim3((f + kWG - 1) / kWG), dim3(kWG), 0, st, nq, f, scratch, out);
+    hipLaunchKernelGGL(k_col_sum_stage2, dim3((f + 31) / 32), dim3(kWG), 0, st, nq, f, scratch, out);
     return hip_fail((int)hipGetLastError(), "col_sum launch");
 }
 
