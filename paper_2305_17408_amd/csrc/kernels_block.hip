@@ -5,86 +5,220 @@
 // The topology of the block uses one-byte block-local column indices.
 // With FUSED the same lanes go on to add their rows' inter-community entries (gathered from
 // global memory), so each output row is written exactly once and no merge pass is needed.
+//
+// Mapping: a team of G lanes owns a contiguous run of the block's rows; a lane owns NV vectors
+// of VEC floats, vector v at feature offset (v*G + lane)*VEC of the tile, so every load of a
+// team is one contiguous G*VEC-float piece of a feature row.  The team's entries are one
+// contiguous range of the topology arrays and are streamed through a 3-deep ring of register
+// chunks (G entries each, fetched ahead of use) independent of the row boundaries; the row
+// pointers of the team's rows sit in its lanes.  The kernel is bound by vector-ALU issue, not
+// by LDS or HBM, which is why a lane carries NV = 2 vectors for wide features (half the
+// shuffles and address arithmetic per FMA).
 #include "kernels_common.h"
 
 namespace ag {
 namespace {
 
-template <int G, int VEC, bool FUSED>
+// Entries lo..hi-1 of a register chunk (lane k of the team holds entry k); feature rows come
+// from the LDS tile.  Entries beyond hi belong to other rows: they are redirected to the zero
+// row of the tile with weight 0, so nothing of them reaches the sum (not even 0 * Inf).
+template <int G, int NV, int VEC>
+__device__ __forceinline__ void chunk_range_lds(int c, float v, int lo, int hi, const float *sH, int gl,
+                                                float (&acc)[NV][VEC])
+{
+    constexpr int FT = G * VEC * NV, U = 4;
+    for (int k0 = lo; k0 < hi; k0 += U) {
+        int row[U];
+        float w[U], h[U][NV][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool ok = k0 + u < hi;
+            const int ck = __shfl(c, (k0 + u) & (G - 1), G);
+            const float vk = __shfl(v, (k0 + u) & (G - 1), G);
+            row[u] = ok ? ck : kMaxBlock;
+            w[u] = ok ? vk : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int q = 0; q < NV; ++q) load_vec<VEC>(sH + row[u] * FT + (q * G + gl) * VEC, h[u][q]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[q][j] = fmaf(w[u], h[u][q][j], acc[q][j]);
+    }
+}
+
+// the same with the feature rows gathered from global memory (U * NV loads in flight per lane)
+template <int G, int NV, int VEC>
+__device__ __forceinline__ void chunk_range_global(int c, float v, int lo, int hi, const float *__restrict__ H,
+                                                   int F, int f, const bool (&fok)[NV], float (&acc)[NV][VEC])
+{
+    constexpr int U = 4;
+    for (int k0 = lo; k0 < hi; k0 += U) {
+        int ck[U];
+        float vk[U], h[U][NV][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ck[u] = __shfl(c, (k0 + u) & (G - 1), G);
+            vk[u] = __shfl(v, (k0 + u) & (G - 1), G);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!(k0 + u < hi)) vk[u] = 0.f;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                if (k0 + u < hi && fok[q]) {
+                    load_vec<VEC>(H + (size_t)ck[u] * F + f + q * G * VEC, h[u][q]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) h[u][q][j] = 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[q][j] = fmaf(vk[u], h[u][q][j], acc[q][j]);
+    }
+}
+
+template <int G, int NV, int VEC, bool FUSED>
 __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t *__restrict__ list,
                                                       CsrDev R, const float *__restrict__ H,
                                                       float *__restrict__ Y, int F)
 {
-    constexpr int FT = G * VEC, TEAMS = kWG / G, U = 4;
-    __shared__ float sH[kMaxBlock * FT];
+    constexpr int FT = G * VEC * NV, TEAMS = kWG / G;
+    static_assert(kMaxBlock / TEAMS + 1 <= G, "row pointers of a team must fit in its lanes");
+    extern __shared__ float sH[];                       // (kMaxBlock + 1) x FT: feature tile + a zero row
     const int tid = threadIdx.x;
     const int b = list[blockIdx.x];
     const int r0 = B.blk_ptr[b], nr = B.blk_ptr[b + 1] - r0;
     const int f0 = blockIdx.y * FT;
-    for (int idx = tid; idx < nr * G; idx += kWG) {
-        const int r = idx / G, g = idx % G, f = f0 + g * VEC;
-        float h[VEC];
-        if (f < F) {
-            load_vec<VEC>(H + (size_t)(r0 + r) * F + f, h);
-        } else {
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) h[j] = 0.f;
-        }
-        store_vec<VEC>(sH + r * FT + g * VEC, h);
-    }
-    __syncthreads();
     const int team = tid / G, gl = tid % G;
-    const int f = f0 + gl * VEC;
-    const bool fok = f < F;
-    for (int r = team; r < nr; r += TEAMS) {
-        const int row = r0 + r;
-        const int beg = B.i_rowptr[row], end = B.i_rowptr[row + 1];
-        float acc[VEC];
+    const int f = f0 + gl * VEC;                        // first feature of vector 0
+    bool fok[NV];
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
-        for (int base = beg; base < end; base += G) {
-            const int e = base + gl;
-            int c = 0;
-            float v = 0.f;
-            if (e < end) {
-                c = B.i_col8[e];
-                v = B.i_val ? B.i_val[e] : 1.f;
-            }
-            const int cnt = min(G, end - base);
-            for (int k0 = 0; k0 < cnt; k0 += U) {
+    for (int q = 0; q < NV; ++q) fok[q] = f + q * G * VEC < F;
+    const int rpt = (nr + TEAMS - 1) / TEAMS;           // rows per team
+    const int first = min(team * rpt, nr);
+    const int myrows = min(rpt, nr - first);
+    const int irp = B.i_rowptr[r0 + first + min(gl, myrows)];
+    const int ie1 = __shfl(irp, myrows, G);
+    int iq = __shfl(irp, 0, G);                         // entry held by lane 0 of ring chunk 0
+    int ic0, ic1, ic2;
+    float iv0, iv1, iv2;
+    auto ld_i = [&](int e, int &c, float &v) {
+        c = 0;
+        v = 0.f;
+        if (e < ie1) {
+            c = B.i_col8[e];
+            v = B.i_val ? B.i_val[e] : 1.f;
+        }
+    };
+    ld_i(iq + gl, ic0, iv0);
+    ld_i(iq + G + gl, ic1, iv1);
+    ld_i(iq + 2 * G + gl, ic2, iv2);
+    int rrp = 0, re1 = 0, rq = 0, rc0 = 0, rc1 = 0, rc2 = 0;
+    float rv0 = 0.f, rv1 = 0.f, rv2 = 0.f;
+    auto ld_r = [&](int e, int &c, float &v) {
+        c = 0;
+        v = 0.f;
+        if (e < re1) {
+            c = R.col[e];
+            v = R.val ? R.val[e] : 1.f;
+        }
+    };
+    if constexpr (FUSED) {
+        rrp = R.rowptr[r0 + first + min(gl, myrows)];
+        re1 = __shfl(rrp, myrows, G);
+        rq = __shfl(rrp, 0, G);
+        ld_r(rq + gl, rc0, rv0);
+        ld_r(rq + G + gl, rc1, rv1);
+        ld_r(rq + 2 * G + gl, rc2, rv2);
+    }
+    stage_tile<FT, VEC>(H, F, r0, nr, nr, f0, sH, tid);
+    for (int j = tid; j < FT; j += kWG) sH[kMaxBlock * FT + j] = 0.f;
+    __syncthreads();
+    for (int i = 0; i < myrows; ++i) {
+        const int row = r0 + first + i;
+        float acc[NV][VEC];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int kk = k0 + u;
-                    const int ck = __shfl(c, kk & (G - 1), G);
-                    const float vk = __shfl(v, kk & (G - 1), G);
-                    if (kk < cnt) {
-                        float h[VEC];
-                        load_vec<VEC>(sH + ck * FT + gl * VEC, h);
+        for (int q = 0; q < NV; ++q)
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) acc[j] = fmaf(vk, h[j], acc[j]);
-                    }
+            for (int j = 0; j < VEC; ++j) acc[q][j] = 0.f;
+        {
+            const int rb = __shfl(irp, i, G), re = __shfl(irp, i + 1, G);
+            int k = rb;
+            while (k < re) {
+                if (k >= iq + G) {                      // move on to the next chunk of the ring
+                    ic0 = ic1; iv0 = iv1; ic1 = ic2; iv1 = iv2;
+                    iq += G;
+                    ld_i(iq + 2 * G + gl, ic2, iv2);
                 }
+                const int hi = min(re, iq + G) - iq;
+                chunk_range_lds<G, NV, VEC>(ic0, iv0, k - iq, hi, sH, gl, acc);
+                k = iq + hi;
             }
         }
         if constexpr (FUSED) {
-            const int rb = R.rowptr[row], re = R.rowptr[row + 1];
-            if (re - rb <= kLongThresh)
-                team_row_gather<G, G, VEC>(R.col, R.val, rb, re, H, F, f, fok, gl, acc);
+            const int rb = __shfl(rrp, i, G), re = __shfl(rrp, i + 1, G);
+            int k = rb;
+            if (re - rb > kLongThresh) k = re;          // long rows: the segment kernels add them
+            while (k < re) {
+                if (k >= rq + 3 * G) {                  // skipped far ahead: restart the ring here
+                    rq = k;
+                    ld_r(rq + gl, rc0, rv0);
+                    ld_r(rq + G + gl, rc1, rv1);
+                    ld_r(rq + 2 * G + gl, rc2, rv2);
+                } else if (k >= rq + G) {
+                    rc0 = rc1; rv0 = rv1; rc1 = rc2; rv1 = rv2;
+                    rq += G;
+                    ld_r(rq + 2 * G + gl, rc2, rv2);
+                    continue;                           // may have to advance once more
+                }
+                const int hi = min(re, rq + G) - rq;
+                chunk_range_global<G, NV, VEC>(rc0, rv0, k - rq, hi, H, F, f, fok, acc);
+                k = rq + hi;
+            }
         }
-        if (fok) store_vec<VEC>(Y + (size_t)row * F + f, acc);
+#pragma unroll
+        for (int q = 0; q < NV; ++q)
+            if (fok[q]) store_vec<VEC>(Y + (size_t)row * F + f + q * G * VEC, acc[q]);
     }
 }
 
-template <int G, int VEC>
+template <int G, int NV, int VEC, bool FUSED>
+int launch_one(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev &R, const float *H, float *Y,
+               int F, hipStream_t st)
+{
+    constexpr int FT = G * VEC * NV;
+    constexpr size_t lds = (size_t)(kMaxBlock + 1) * FT * sizeof(float);
+    static bool prepared = false;                       // per instantiation
+    if (!prepared) {
+        if (lds > 65536) {
+            int rc = hip_fail((int)hipFuncSetAttribute((const void *)k_block_sparse<G, NV, VEC, FUSED>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+                              "LDS size attribute");
+            if (rc) return rc;
+        }
+        prepared = true;
+    }
+    dim3 grid(nlist, (F + FT - 1) / FT);
+    hipLaunchKernelGGL((k_block_sparse<G, NV, VEC, FUSED>), grid, dim3(kWG), lds, st, B, list, R, H, Y, F);
+    return hip_fail((int)hipGetLastError(), "block_sparse launch");
+}
+
+template <int G, int NV, int VEC>
 int run(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev *rem, const float *H,
         float *Y, int F, hipStream_t st)
 {
-    dim3 grid(nlist, (F + G * VEC - 1) / (G * VEC));
-    if (rem)
-        hipLaunchKernelGGL((k_block_sparse<G, VEC, true>), grid, dim3(kWG), 0, st, B, list, *rem, H, Y, F);
-    else
-        hipLaunchKernelGGL((k_block_sparse<G, VEC, false>), grid, dim3(kWG), 0, st, B, list, CsrDev(), H, Y, F);
-    return hip_fail((int)hipGetLastError(), "block_sparse launch");
+    if (rem) return launch_one<G, NV, VEC, true>(B, list, nlist, *rem, H, Y, F, st);
+    return launch_one<G, NV, VEC, false>(B, list, nlist, CsrDev(), H, Y, F, st);
 }
 
 }  // namespace
@@ -94,16 +228,19 @@ int launch_block_sparse(const BlocksDev &B, const int32_t *list, int32_t nlist, 
 {
     if (nlist <= 0) return AG_OK;
     hipStream_t st = (hipStream_t)stream;
-    const int VEC = (F % 4 == 0) ? 4 : 1;
-    const int need = (F + VEC - 1) / VEC, cap = (VEC == 4) ? 32 : 64;
-    int G = 4;
-    while (G < need && G < cap) G <<= 1;
-#define AG_CASE(g, v) if (G == g && VEC == v) return run<g, v>(B, list, nlist, fused_rem, H, Y, F, st);
-    AG_CASE(4, 4) AG_CASE(8, 4) AG_CASE(16, 4) AG_CASE(32, 4)
-    AG_CASE(4, 1) AG_CASE(8, 1) AG_CASE(16, 1) AG_CASE(32, 1) AG_CASE(64, 1)
-#undef AG_CASE
-    set_error("block_sparse: no kernel shape for this feature width");
-    return AG_ERR_UNSUPPORTED;
+    if (F % 4 == 0) {
+        const int need = F / 4;                         // float4 vectors per row
+        if (need >= 32) return run<16, 2, 4>(B, list, nlist, fused_rem, H, Y, F, st);
+        if (need >= 16) return run<8, 2, 4>(B, list, nlist, fused_rem, H, Y, F, st);
+        if (need > 8) return run<16, 1, 4>(B, list, nlist, fused_rem, H, Y, F, st);
+        if (need > 4) return run<8, 1, 4>(B, list, nlist, fused_rem, H, Y, F, st);
+        return run<4, 1, 4>(B, list, nlist, fused_rem, H, Y, F, st);
+    }
+    if (F > 32) return run<64, 1, 1>(B, list, nlist, fused_rem, H, Y, F, st);
+    if (F > 16) return run<32, 1, 1>(B, list, nlist, fused_rem, H, Y, F, st);
+    if (F > 8) return run<16, 1, 1>(B, list, nlist, fused_rem, H, Y, F, st);
+    if (F > 4) return run<8, 1, 1>(B, list, nlist, fused_rem, H, Y, F, st);
+    return run<4, 1, 1>(B, list, nlist, fused_rem, H, Y, F, st);
 }
 
 }  // namespace ag

@@ -40,18 +40,80 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
     return x * per + (x < rem ? x : rem) + i;
 }
 
-// Accumulate entries [beg,end) of one CSR row into acc.  A team of W lanes (W/G lane groups
-// of G lanes, each lane owning VEC features starting at column f) loads W (column, value)
-// pairs at a time, hands them round with lane shuffles, and every lane group gathers the
-// feature rows of its share of the entries.  All W lanes of the team must call this together.
+// Copy rows [r0, r0+nr) x columns [f0, f0+FT) of the row-major matrix H (F columns) into the LDS
+// tile sH[row][FT]; rows nr..pad_rows-1 and columns beyond F are zero-filled.  All loads of a
+// thread are issued before its first LDS store, so a tile costs one memory latency, not one per
+// row.  Must be called by the whole work-group; the caller synchronises afterwards.
+template <int FT, int VEC>
+__device__ __forceinline__ void stage_tile(const float *__restrict__ H, int F, int r0, int nr, int pad_rows,
+                                           int f0, float *sH, int tid)
+{
+    constexpr int UPR = FT / VEC;                       // load units per tile row
+    constexpr int ITER = (kMaxBlock * UPR + kWG - 1) / kWG;
+    float h[ITER][VEC];
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int idx = tid + it * kWG, r = idx / UPR, ff = f0 + (idx % UPR) * VEC;
+        if (r < nr && ff < F) {
+            load_vec<VEC>(H + (size_t)(r0 + r) * F + ff, h[it]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) h[it][j] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int idx = tid + it * kWG, r = idx / UPR;
+        if (r < pad_rows) store_vec<VEC>(sH + r * FT + (idx % UPR) * VEC, h[it]);
+    }
+}
+
+// One chunk of a CSR row held in registers: lane tl of the team holds entry tl's column `c` and
+// value `v` (cnt <= W entries are valid).  The W/G lane groups (G lanes, each lane owning VEC
+// features starting at column f) pass the entries round with lane shuffles and gather the
+// feature rows of their share from global memory, 4 independent loads in flight per lane.
+// All W lanes of the team must call this together.
+template <int G, int W, int VEC>
+__device__ __forceinline__ void team_chunk_gather(int c, float v, int cnt, const float *__restrict__ H,
+                                                  int F, int f, bool fok, int tl, float (&acc)[VEC])
+{
+    constexpr int NSG = W / G, U = 4;
+    const int sg = tl / G;
+    for (int k0 = 0; k0 < cnt; k0 += NSG * U) {
+        int ck[U];
+        float vk[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kk = k0 + u * NSG + sg;
+            ck[u] = __shfl(c, kk & (W - 1), W);
+            vk[u] = __shfl(v, kk & (W - 1), W);
+        }
+        float h[U][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kk = k0 + u * NSG + sg;
+            if (kk < cnt && fok) {
+                load_vec<VEC>(H + (size_t)ck[u] * F + f, h[u]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) h[u][j] = 0.f;
+                vk[u] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[j] = fmaf(vk[u], h[u][j], acc[j]);
+    }
+}
+
+// Accumulate entries [beg,end) of one CSR row into acc, W entries per chunk (see above).
 template <int G, int W, int VEC>
 __device__ __forceinline__ void team_row_gather(const int32_t *__restrict__ col,
                                                 const float *__restrict__ val, int beg, int end,
                                                 const float *__restrict__ H, int F, int f, bool fok,
                                                 int tl, float (&acc)[VEC])
 {
-    constexpr int NSG = W / G, U = 4;
-    const int sg = tl / G;
     for (int base = beg; base < end; base += W) {
         const int e = base + tl;
         int c = 0;
@@ -60,33 +122,7 @@ __device__ __forceinline__ void team_row_gather(const int32_t *__restrict__ col,
             c = col[e];
             v = val ? val[e] : 1.f;
         }
-        const int cnt = min(W, end - base);
-        for (int k0 = 0; k0 < cnt; k0 += NSG * U) {
-            int ck[U];
-            float vk[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int kk = k0 + u * NSG + sg;
-                ck[u] = __shfl(c, kk & (W - 1), W);
-                vk[u] = __shfl(v, kk & (W - 1), W);
-            }
-            float h[U][VEC];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int kk = k0 + u * NSG + sg;
-                if (kk < cnt && fok) {
-                    load_vec<VEC>(H + (size_t)ck[u] * F + f, h[u]);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) h[u][j] = 0.f;
-                    vk[u] = 0.f;
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) acc[j] = fmaf(vk[u], h[u][j], acc[j]);
-        }
+        team_chunk_gather<G, W, VEC>(c, v, min(W, end - base), H, F, f, fok, tl, acc);
     }
 }
 

@@ -28,10 +28,8 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, const float *_
     const int r0 = B.blk_ptr[b], nr = B.blk_ptr[b + 1] - r0;
     const int f0 = blockIdx.y * FT;
     const int kpad = (nr + 31) & ~31;                 // source rows rounded up, extras are zero
-    for (int idx = tid; idx < kpad * FT; idx += kWG) {
-        const int r = idx / FT, f = f0 + idx % FT;
-        sH[idx] = (r < nr && f < F) ? H[(size_t)(r0 + r) * F + f] : 0.f;
-    }
+    if (F % 4 == 0) stage_tile<FT, 4>(H, F, r0, nr, kpad, f0, sH, tid);
+    else stage_tile<FT, 1>(H, F, r0, nr, kpad, f0, sH, tid);
     __syncthreads();
     const int w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
     if (32 * w >= nr) return;
