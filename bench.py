@@ -141,16 +141,22 @@ def main():
         step()
     prof = [ag.ag_plan_profile(plan, d) for d in (0, 1)]
     ag.ag_plan_set_profiling(plan, False)
-    cls_names = {0: "dense-class blocks", 1: "sparse-class blocks", 2: "remainder CSR"}
+    compose = prof[0]["compose"]
+    if compose == 1:
+        cls_names = {0: "fused block kernel (all blocks: intra from LDS + their remainder rows)",
+                     1: "(unused)", 2: "tail rows + long-row segments"}
+    elif compose == 2:
+        cls_names = {0: "(unused)", 1: "(unused)", 2: "one CSR over the whole reordered matrix"}
+    else:
+        cls_names = {0: "dense-class blocks", 1: "sparse-class blocks", 2: "remainder CSR"}
     per_class = {}
     for c in range(3):
         ms = sum(p["class_ms"][c] for p in prof)
         calls = sum(p["calls"] for p in prof)
         per_class[c] = ms / max(1, calls)
     dom = max(per_class, key=per_class.get)
-    compose = prof[0]["compose"]
     if compose == 1 and dom == 0:
-        dom_name = "k_block_sparse<fused> (intra blocks + their remainder rows)"
+        dom_name = "k_block_sparse<..., FUSED=true>"
     elif dom == 2:
         dom_name = "k_csr_rows (+ long-row segments)"
     else:
@@ -159,11 +165,20 @@ def main():
     achieved = abytes / (per_class[dom] * 1e-3) / 1e9 if per_class[dom] > 0 else 0.0
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(args.config, F, compose) if dom == 2 else None,
+                "traffic": measured_traffic(args.config, F, compose),
                 "kernel": dom_name, "class": cls_names[dom], "avg_launch_ms": round(per_class[dom], 5),
                 "algorithmic_bytes_per_launch": int(abytes),
                 "per_class_ms": {cls_names[c]: round(per_class[c], 5) for c in per_class}}
     log(f"[bench] roofline: {roofline}")
+    # the sparse-remainder kernel on its own, from the selector's timed trials (SPLIT composition)
+    rem_ms = min((t for t in sel[0]["trial_ms"][2][:2] if t > 0), default=0.0)
+    rem_bytes = algorithmic_bytes(st, F, 0, 2)
+    remainder = {"kernel": "k_csr_rows on the inter-community CSR (accumulating onto block rows)",
+                 "median_trial_ms": round(rem_ms, 5), "algorithmic_bytes_per_launch": int(rem_bytes),
+                 "achieved": round(rem_bytes / (rem_ms * 1e-3) / 1e9, 1) if rem_ms > 0 else None,
+                 "frac": round(rem_bytes / (rem_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if rem_ms > 0 else None,
+                 "unit": "GB/s", "peak": HBM_PEAK_GBS}
+    compose_ms = dict(zip(("split", "fused", "full_csr"), [round(t, 5) for t in sel[0]["trial_ms"][3][:3]]))
 
     out = {
         "metric": "aggregation GFLOP/s (fwd+bwd SpMM, fp32)", "value": round(gflops, 2), "unit": "GFLOP/s",
@@ -180,6 +195,10 @@ def main():
                                     "n_long_rows", "sec_reorder", "sec_split", "sec_build", "sec_upload",
                                     "device_bytes")},
         "roofline": roofline,
+        "remainder_path": remainder,
+        "selector_trial_ms": {"compositions_fwd": compose_ms,
+                              "dense_class_fwd": {"block_sparse": round(sel[0]["trial_ms"][0][0], 5),
+                                                  "dense_mfma": round(sel[0]["trial_ms"][0][1], 5)}},
     }
 
     # ms per 2-layer GCN training step (only defined for the GCN workload)

@@ -230,7 +230,8 @@ int launch_block_sparse(const BlocksDev &B, const int32_t *list, int32_t nlist, 
     hipStream_t st = (hipStream_t)stream;
     if (F % 4 == 0) {
         const int need = F / 4;                         // float4 vectors per row
-        if (need >= 32) return run<16, 2, 4>(B, list, nlist, fused_rem, H, Y, F, st);
+        // 64-feature tiles (33 KB of LDS, 4 work-groups per CU) beat 128-feature tiles (2 per CU)
+        if (need >= 32) return run<8, 2, 4>(B, list, nlist, fused_rem, H, Y, F, st);
         if (need >= 16) return run<8, 2, 4>(B, list, nlist, fused_rem, H, Y, F, st);
         if (need > 8) return run<16, 1, 4>(B, list, nlist, fused_rem, H, Y, F, st);
         if (need > 4) return run<8, 1, 4>(B, list, nlist, fused_rem, H, Y, F, st);
