@@ -28,7 +28,7 @@ def log(*a):
 
 
 def algorithmic_bytes(st, F, compose, cls):
-    """Algorithmic HBM bytes of one launch of the kernel(s) of class `cls` (see DESIGN.md).
+    """Algorithmic HBM bytes of one launch of the kernel(s) of class `cls`.
 
     Remainder: its CSR arrays once, one feature-row fetch per stored entry (the sources of the
     inter-community subgraph have no locality by construction), one write of every output
@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (0-based)")
+    ap.add_argument("--config", type=int, default=3, help="index of the benchmark workload (0-based, see ag_inputs.CONFIGS)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN training-step timing")
     args = ap.parse_args()

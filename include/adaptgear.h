@@ -119,6 +119,9 @@ int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int3
 /* kernels for the remainder: lanes cooperating on one row */
 #define AG_K_CSR_NARROW       0   /* one feature-wide lane group per row (Sec. 3.2, CSR inter)    */
 #define AG_K_CSR_WIDE         1   /* several lane groups per row, neighbours interleaved          */
+#define AG_K_COO              2   /* edge-parallel with fp32 atomics (Algorithm 1 + edge value);  *
+                                   * summation order varies between runs; used in AG_COMPOSE_SPLIT *
+                                   * only (the other compositions fall back to AG_K_CSR_NARROW)    */
 /* compositions */
 #define AG_COMPOSE_SPLIT      0   /* block kernels write Y, the remainder kernel accumulates      */
 #define AG_COMPOSE_FUSED      1   /* sparse-block kernel also walks its rows' remainder           */

@@ -71,7 +71,8 @@ void build_block_formats(const ReorderResult &r, const std::vector<int32_t> &den
 struct CsrDev {
     const int32_t *rowptr = nullptr, *col = nullptr;
     const float   *val = nullptr;          // nullptr = unit weights
-    int32_t n = 0;
+    const int32_t *row = nullptr;          // row of every entry (COO form), only where the COO kernel may run
+    int32_t n = 0, nnz = 0;
     const int32_t *seg_row = nullptr, *seg_beg = nullptr, *seg_end = nullptr;
     int32_t nseg = 0;
     const int32_t *lr_row = nullptr, *lr_seg0 = nullptr;
@@ -103,6 +104,10 @@ int launch_csr_rows(const CsrDev &A, const float *H, float *Y, int32_t F, int32_
 // All long rows of `A`: segments -> partial[nseg][F] -> Y (rows below acc_below accumulate).
 int launch_csr_long(const CsrDev &A, const float *H, float *Y, int32_t F, float *partial,
                     int32_t acc_below, void *stream);
+// kernels_coo.hip
+// Edge-parallel accumulation of all entries of `A` (needs A.row) onto Y with fp32 atomics; rows
+// from zero_from on are cleared first (the rows nobody wrote before).
+int launch_coo(const CsrDev &A, const float *H, float *Y, int32_t F, int32_t zero_from, void *stream);
 // kernels_block.hip
 int launch_block_sparse(const BlocksDev &B, const int32_t *list, int32_t nlist, const CsrDev *fused_rem,
                         const float *H, float *Y, int32_t F, void *stream);

@@ -80,10 +80,17 @@ struct Topology {
         return AG_OK;
     }
 
-    int upload_csr(const HostCsr &A, const HostDir::Segs &s, CsrDev &D)
+    int upload_csr(const HostCsr &A, const HostDir::Segs &s, CsrDev &D, bool with_rows)
     {
         int rc;
         D.n = (int32_t)A.n;
+        D.nnz = (int32_t)A.nnz();
+        if (with_rows) {                                  // COO form: the row of every entry
+            std::vector<int32_t> rows((size_t)A.nnz());
+            for (int64_t i = 0; i < A.n; ++i)
+                std::fill(rows.begin() + A.rowptr[i], rows.begin() + A.rowptr[i + 1], (int32_t)i);
+            if ((rc = upload(rows, D.row))) return rc;
+        }
         if ((rc = upload(A.rowptr, D.rowptr))) return rc;
         if ((rc = upload(A.col, D.col))) return rc;
         if (!A.val.empty()) { if ((rc = upload(A.val, D.val))) return rc; }
@@ -103,8 +110,8 @@ struct Topology {
         HostDir &H = h[k];
         DevDir &D = d[k];
         int rc;
-        if ((rc = upload_csr(H.full, H.segs_full, D.full))) return rc;
-        if ((rc = upload_csr(H.inter, H.segs_inter, D.inter))) return rc;
+        if ((rc = upload_csr(H.full, H.segs_full, D.full, false))) return rc;
+        if ((rc = upload_csr(H.inter, H.segs_inter, D.inter, true))) return rc;
         BlocksDev &B = D.blk;
         B.blk_ptr = blk_ptr_dev;
         B.nb = r.n_blocks;
@@ -134,6 +141,7 @@ struct Selector {
     int cand = 0, rep = 0, calls = 0;
     std::vector<float> samples[AG_NUM_CLS][4];
     float median_ms[AG_NUM_CLS][4];
+    float best_ms[AG_NUM_CLS];      // fastest finished candidate so far (early abandon of hopeless ones)
     float total_trial_ms = 0.f;
 
     void reset(bool keep_forced)
@@ -141,6 +149,7 @@ struct Selector {
         for (int c = 0; c < AG_NUM_CLS; ++c) {
             if (!keep_forced) forced[c] = -1;
             choice[c] = 0;
+            best_ms[c] = -1.f;
             for (int k = 0; k < 4; ++k) { samples[c][k].clear(); median_ms[c][k] = -1.f; }
         }
         phase = 0; cand = 0; rep = 0; total_trial_ms = 0.f;
@@ -192,7 +201,7 @@ void init_selector(ag_plan *p, int dir, bool keep_forced)
     const Topology &t = *p->topo;
     s.ncand[AG_CLS_BLOCKS_DENSE] = t.dense_blocks.empty() ? 1 : 2;
     s.ncand[AG_CLS_BLOCKS_SPARSE] = 1;
-    s.ncand[AG_CLS_REMAINDER] = 2;
+    s.ncand[AG_CLS_REMAINDER] = 3;
     s.ncand[AG_CLS_COMPOSE] = (t.r.n_blocks > 0) ? 3 : 1;
 }
 
@@ -223,6 +232,7 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
     const DevDir &D = t.d[dir_idx];
     const int32_t F = p->F, n = (int32_t)t.n, nbr = D.blk.n_block_rows;
     const bool wide = k[AG_CLS_REMAINDER] == AG_K_CSR_WIDE;
+    const bool coo = k[AG_CLS_REMAINDER] == AG_K_COO;     // only the SPLIT composition has a COO form
     int rc = AG_OK;
     if (ev) (void)hipEventRecord(ev[0], st);
     switch (k[AG_CLS_COMPOSE]) {
@@ -246,8 +256,12 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
         if (ev) (void)hipEventRecord(ev[1], st);
         if ((rc = launch_block_sparse(D.blk, D.blk.list_sparse, D.blk.n_sparse, nullptr, H, Y, F, st))) return rc;
         if (ev) (void)hipEventRecord(ev[2], st);
-        if ((rc = launch_csr_rows(D.inter, H, Y, F, 0, n, nbr, wide, st))) return rc;
-        if ((rc = launch_csr_long(D.inter, H, Y, F, p->partial, nbr, st))) return rc;
+        if (coo) {
+            if ((rc = launch_coo(D.inter, H, Y, F, nbr, st))) return rc;
+        } else {
+            if ((rc = launch_csr_rows(D.inter, H, Y, F, 0, n, nbr, wide, st))) return rc;
+            if ((rc = launch_csr_long(D.inter, H, Y, F, p->partial, nbr, st))) return rc;
+        }
         break;
     }
     if (ev) (void)hipEventRecord(ev[3], st);
@@ -321,7 +335,24 @@ void record_trial(ag_plan *p, Selector &s, const int *k, hipEvent_t *ev)
     (void)hipEventElapsedTime(&ms[3], ev[0], ev[3]);
     s.total_trial_ms += ms[3];
     const bool timed = s.rep > 0;                       // rep 0 is the warm-up
-    if (timed) {
+    // A candidate whose warm-up run is already 4x slower than the best finished one is hopeless:
+    // its warm-up time is kept as its only sample and the timed repetitions are skipped.
+    bool hopeless = false;
+    if (!timed) {
+        if (s.phase == 0) {
+            bool any = false, all_slow = true;
+            for (int c = 0; c < AG_CLS_COMPOSE; ++c)
+                if (s.forced[c] < 0 && s.cand < s.ncand[c] && s.ncand[c] > 1) {
+                    any = true;
+                    if (!(s.best_ms[c] > 0 && ms[c] > 4.f * s.best_ms[c])) all_slow = false;
+                }
+            hopeless = any && all_slow;
+        } else {
+            const float b = s.best_ms[AG_CLS_COMPOSE];
+            hopeless = b > 0 && ms[3] > 4.f * b;
+        }
+    }
+    if (timed || hopeless) {
         if (s.phase == 0) {
             for (int c = 0; c < AG_CLS_COMPOSE; ++c)
                 if (s.forced[c] < 0 && s.cand < s.ncand[c]) s.samples[c][k[c]].push_back(ms[c]);
@@ -329,7 +360,17 @@ void record_trial(ag_plan *p, Selector &s, const int *k, hipEvent_t *ev)
             s.samples[AG_CLS_COMPOSE][k[AG_CLS_COMPOSE]].push_back(ms[3]);
         }
     }
-    if (++s.rep > p->trials) { s.rep = 0; ++s.cand; }
+    if (++s.rep > p->trials || hopeless) {
+        // candidate finished: remember the fastest median per class
+        for (int c = 0; c < AG_NUM_CLS; ++c) {
+            if ((s.phase == 0) == (c == AG_CLS_COMPOSE)) continue;
+            if (s.forced[c] >= 0 || s.cand >= s.ncand[c]) continue;
+            const float m = median_of(s.samples[c][k[c]]);
+            if (m > 0 && (s.best_ms[c] < 0 || m < s.best_ms[c])) s.best_ms[c] = m;
+        }
+        s.rep = 0;
+        ++s.cand;
+    }
 }
 
 constexpr int kProfRing = 64;
@@ -535,7 +576,7 @@ int ag_plan_force_kernels(ag_plan *p, int32_t cls, int32_t dir, int32_t kernel_i
         set_error("bad class or direction");
         return AG_ERR_INVALID;
     }
-    static const int limit[AG_NUM_CLS] = {2, 1, 2, 3};
+    static const int limit[AG_NUM_CLS] = {2, 1, 3, 3};
     if (kernel_id < -1 || kernel_id >= 4) { set_error("kernel id out of range"); return AG_ERR_INVALID; }
     if (kernel_id >= limit[cls]) { set_error("kernel id not available for this class"); return AG_ERR_UNSUPPORTED; }
     Selector &s = p->sel[dir];

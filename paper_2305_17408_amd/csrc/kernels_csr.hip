@@ -24,6 +24,7 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(CsrDev A, const float *__restr
     if (row >= row_end) return;                       // the whole team leaves together
     const int beg = A.rowptr[row], end = A.rowptr[row + 1];
     if (end - beg > kLongThresh) return;              // served by the segment kernels
+    if (beg == end && row < acc_below) return;        // nothing to add to a row that is already written
     const int f = blockIdx.y * (G * VEC) + gl * VEC;
     const bool fok = f < F;
     float acc[VEC];

@@ -17,7 +17,10 @@ COMBOS = {
     "split_sparse_wide": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_WIDE),
     "split_dense_narrow": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_DENSE, ag.AG_K_CSR_NARROW),
     "fused_narrow": (ag.AG_COMPOSE_FUSED, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_NARROW),
+    "split_sparse_coo": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_SPARSE, ag.AG_K_COO),
 }
+# combinations whose summation order is fixed (no atomics): bitwise reproducible run to run
+DETERMINISTIC = [k for k in COMBOS if not k.endswith("coo")]
 
 
 def say(*a):

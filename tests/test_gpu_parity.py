@@ -9,7 +9,7 @@ import oracle
 import paper_2305_17408_amd as ag
 from ag_inputs import (config_graph, planted_partition, gcn_normalise, row_normalise, directed_random,
                        mixed_density, from_edges, features)
-from gpu_util import Case, COMBOS, check, force, say
+from gpu_util import Case, COMBOS, DETERMINISTIC, check, force, say
 
 pytestmark = pytest.mark.gpu
 
@@ -108,7 +108,7 @@ def test_exact_cases():
 def test_runs_are_bitwise_reproducible():
     g = config_graph(2, scale=1 / 32)
     c = Case(g, 64)
-    for name in COMBOS:
+    for name in DETERMINISTIC:
         force(c.plan, name, 0)
         a = c.forward().cpu().numpy()
         b = c.forward().cpu().numpy()
@@ -156,7 +156,7 @@ def test_adaptive_selector_freezes_and_stays_correct():
     say("selector:", info)
     assert info["choice"][ag.AG_CLS_COMPOSE] in (0, 1, 2)
     assert info["choice"][ag.AG_CLS_BLOCKS_DENSE] in (0, 1)
-    assert info["choice"][ag.AG_CLS_REMAINDER] in (0, 1)
+    assert info["choice"][ag.AG_CLS_REMAINDER] in (0, 1, 2)
     check(c.forward(), c.Yref, c.Sy, "after freeze")
     # backward has its own state
     assert not ag.ag_plan_selector_info(c.plan, 1)["frozen"]
