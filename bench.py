@@ -62,6 +62,53 @@ def measured_traffic(config, F, compose):
     return None
 
 
+def brief(index, steps):
+    """Short measurement of another workload: ms per aggregation, selector timings, plan cost."""
+    import torch
+    import paper_2305_17408_amd as ag
+    from ag_inputs import config_graph, CONFIGS, features
+    cfg = CONFIGS[index]
+    F = cfg["F"]
+    g = config_graph(index)
+    t0 = time.time()
+    plan = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, F, layout=ag.AG_LAYOUT_REORDERED)
+    t_plan = time.time() - t0
+    st = ag.ag_plan_stats(plan)
+    H = torch.from_numpy(features(g.n, F, 7)).cuda()
+    G = torch.from_numpy(features(g.n, F, 8)).cuda()
+    Y, dH = torch.empty_like(H), torch.empty_like(H)
+    n = 0
+    while n < 200 and not (ag.ag_plan_selector_info(plan, 0)["frozen"] and ag.ag_plan_selector_info(plan, 1)["frozen"]):
+        ag.ag_aggregate(plan, H, Y)
+        ag.ag_aggregate_t(plan, G, dH)
+        n += 1
+    for _ in range(5):
+        ag.ag_aggregate(plan, H, Y)
+        ag.ag_aggregate_t(plan, G, dH)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ag.ag_aggregate(plan, H, Y)
+        ag.ag_aggregate_t(plan, G, dH)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    sel = ag.ag_plan_selector_info(plan, 0)
+    ag.ag_plan_destroy(plan)
+    compulsory = 2 * (4 * (g.n + 1) + (4 + (0 if g.vals is None else 4)) * g.nnz + 8 * g.n * F)
+    t = sel["trial_ms"]
+    log(f"[bench] configs[{index}] {cfg['name']}: {ms:.4f} ms/step, choice {sel['choice']}")
+    return {"workload": f"configs[{index}] {cfg['name']}", "n": g.n, "nnz": g.nnz, "F": F,
+            "ms_per_step": round(ms, 5), "gflops": round(4.0 * g.nnz * F / ms / 1e6, 1),
+            "effective_hbm_gbs": round(compulsory / ms / 1e6, 1), "selector_choice_fwd": sel["choice"],
+            "trial_ms_fwd": {"dense_class": [round(x, 5) for x in t[0][:2]], "sparse_class": round(t[1][0], 5),
+                             "remainder": [round(x, 5) for x in t[2][:3]],
+                             "compose_split_fused_full": [round(x, 5) for x in t[3][:3]]},
+            "plan_create_s": round(t_plan, 2), "nnz_intra": st["nnz_intra"], "nnz_inter": st["nnz_inter"],
+            "n_blocks": st["n_blocks"], "n_dense_blocks": st["n_dense_blocks"], "n_long_rows": st["n_long_rows"],
+            "density_full": st["density_full"], "density_intra": st["density_intra"],
+            "density_inter": st["density_inter"], "plan_device_bytes": st["device_bytes"]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +117,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="index of the benchmark workload (0-based, see ag_inputs.CONFIGS)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN training-step timing")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time the other four workloads (short runs) and add them under 'other_workloads'")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path is single-GPU by design); "
@@ -250,6 +299,8 @@ def main():
                                          f"{cpu_s:.2f} s, fp64, OpenMP"}
         log(f"[bench] cpu oracle: {cpu_s:.2f}s")
     ag.ag_plan_destroy(plan)
+    if args.all_configs:
+        out["other_workloads"] = [brief(i, max(10, args.steps // 2)) for i in range(len(CONFIGS)) if i != args.config]
     print(json.dumps(out), flush=True)
 
 
