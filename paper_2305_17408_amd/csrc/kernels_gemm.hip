@@ -152,13 +152,23 @@ __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, co
 __global__ __launch_bounds__(kWG) void k_sum_partials(int nchunks, int64_t count,
                                                       const float *__restrict__ part, float *__restrict__ C)
 {
-    const int64_t i = (int64_t)blockIdx.x * kWG + threadIdx.x;
-    if (i >= count) return;
+    // 32 outputs per work-group, 8 slices of the partials per output, combined through LDS in a
+    // fixed order (bitwise reproducible)
+    __shared__ float red[kWG];
+    const int64_t i = (int64_t)blockIdx.x * 32 + (threadIdx.x & 31);
+    const int slice = threadIdx.x >> 5;
     float s = 0.f;
-    for (int q = 0; q < nchunks; ++q) s += part[(size_t)q * count + i];
-    C[i] = s;
+    if (i < count)
+        for (int q = slice; q < nchunks; q += 8) s += part[(size_t)q * count + i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x < 32 && i < count) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t += red[k * 32 + threadIdx.x];
+        C[i] = t;
+    }
 }
-
 
 // ------------------------------------------------------------------------------------------
 // C[N x n] = epilogue(A[N x k] W[k x n])
@@ -290,37 +300,48 @@ __global__ __launch_bounds__(kWG) void k_gemm_nn_smallk(const float *__restrict_
     const int64_t rb = (int64_t)blockIdx.x * rows_per_wg;
     const int64_t re = min(N, rb + rows_per_wg);
     const bool vec = (n % 4 == 0), va = (k % 4 == 0);
-    for (int64_t row = rb + sub; row < re; row += rows_at_once) {
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    constexpr int RU = 2;                                // rows in flight per thread
+    for (int64_t row0 = rb + sub; row0 < re; row0 += (int64_t)RU * rows_at_once) {
+        float4 a[RU][KMAX / 4], mk[RU];
 #pragma unroll
-        for (int q4 = 0; q4 < KMAX; q4 += 4) {
-            const float4 a = guarded_load4(A, row, N, q4, k, va);
-            const float av[4] = {a.x, a.y, a.z, a.w};
+        for (int u = 0; u < RU; ++u) {
+            const int64_t row = row0 + (int64_t)u * rows_at_once;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (q4 + j < KMAX) {
+            for (int q4 = 0; q4 < KMAX; q4 += 4) a[u][q4 / 4] = guarded_load4(A, row, re, q4, k, va);
+            mk[u] = make_float4(1.f, 1.f, 1.f, 1.f);
+            if constexpr (EPI == EPI_RELU_MASK) mk[u] = guarded_load4(aux, row, re, c, n, vec);
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const int64_t row = row0 + (int64_t)u * rows_at_once;
+            if (row >= re) break;
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int q4 = 0; q4 < KMAX; q4 += 4) {
+                const float av[4] = {a[u][q4 / 4].x, a[u][q4 / 4].y, a[u][q4 / 4].z, a[u][q4 / 4].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
                     acc.x = fmaf(av[j], wreg[q4 + j].x, acc.x);
                     acc.y = fmaf(av[j], wreg[q4 + j].y, acc.y);
                     acc.z = fmaf(av[j], wreg[q4 + j].z, acc.z);
                     acc.w = fmaf(av[j], wreg[q4 + j].w, acc.w);
                 }
             }
-        }
-        if constexpr (EPI == EPI_BIAS_RELU) {
-            acc.x = fmaxf(acc.x + bias.x, 0.f); acc.y = fmaxf(acc.y + bias.y, 0.f);
-            acc.z = fmaxf(acc.z + bias.z, 0.f); acc.w = fmaxf(acc.w + bias.w, 0.f);
-        }
-        if constexpr (EPI == EPI_RELU_MASK) {
-            const float4 mk = guarded_load4(aux, row, N, c, n, vec);
-            acc.x = mk.x > 0.f ? acc.x : 0.f; acc.y = mk.y > 0.f ? acc.y : 0.f;
-            acc.z = mk.z > 0.f ? acc.z : 0.f; acc.w = mk.w > 0.f ? acc.w : 0.f;
-        }
-        float *o = C + row * n + c;
-        if (vec && c + 3 < n) {
-            *reinterpret_cast<float4 *>(o) = acc;
-        } else {
-            const float ov[4] = {acc.x, acc.y, acc.z, acc.w};
-            for (int j = 0; j < 4 && c + j < n; ++j) o[j] = ov[j];
+            if constexpr (EPI == EPI_BIAS_RELU) {
+                acc.x = fmaxf(acc.x + bias.x, 0.f); acc.y = fmaxf(acc.y + bias.y, 0.f);
+                acc.z = fmaxf(acc.z + bias.z, 0.f); acc.w = fmaxf(acc.w + bias.w, 0.f);
+            }
+            if constexpr (EPI == EPI_RELU_MASK) {
+                acc.x = mk[u].x > 0.f ? acc.x : 0.f; acc.y = mk[u].y > 0.f ? acc.y : 0.f;
+                acc.z = mk[u].z > 0.f ? acc.z : 0.f; acc.w = mk[u].w > 0.f ? acc.w : 0.f;
+            }
+            float *o = C + row * n + c;
+            if (vec && c + 3 < n) {
+                *reinterpret_cast<float4 *>(o) = acc;
+            } else {
+                const float ov[4] = {acc.x, acc.y, acc.z, acc.w};
+                for (int j = 0; j < 4 && c + j < n; ++j) o[j] = ov[j];
+            }
         }
     }
 }
@@ -329,7 +350,7 @@ template <int EPI>
 void run_nn(int64_t N, int k, int n, const float *A, const float *W, float *C, const float *aux, hipStream_t st)
 {
     if (k <= 16 && n <= 4 * kWG) {
-        const int rows_per_wg = 64;
+        const int rows_per_wg = 512;                    // amortises the per-thread load of its W slice
         hipLaunchKernelGGL((k_gemm_nn_smallk<16, EPI>), dim3((unsigned)((N + rows_per_wg - 1) / rows_per_wg)),
                            dim3(kWG), 0, st, A, W, C, N, k, n, aux, rows_per_wg);
         return;
@@ -371,10 +392,10 @@ int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float 
         hipLaunchKernelGGL((k_gemm_tn<4, 1, 2, 1>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     }
     const int64_t count = (int64_t)m * n;
-    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + kWG - 1) / kWG)), dim3(kWG), 0, st, nchunks,
+    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 31) / 32)), dim3(kWG), 0, st, nchunks,
                        count, scratch, C);
     if (colsum)
-        hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + kWG - 1) / kWG)), dim3(kWG), 0, st, nchunks,
+        hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 31) / 32)), dim3(kWG), 0, st, nchunks,
                            (int64_t)n, cs_part, colsum);
     return hip_fail((int)hipGetLastError(), "gemm_tn launch");
 }

@@ -60,7 +60,9 @@ __global__ __launch_bounds__(kWG) void k_relu_grad(int64_t count, const float *_
 }
 
 // One thread per vertex: z = Zin + bias; row loss = logsumexp(z) - z[label] (max-subtracted);
-// dZ = (softmax(z) - onehot) / n.  Zout (optional) receives z.
+// dZ = (softmax(z) - onehot) / n.  Zout (optional) receives z.  CMAX > 0: the row (c <= CMAX,
+// c % 4 == 0) is held in registers and moved with 16-byte loads and stores.
+template <int CMAX>
 __global__ __launch_bounds__(kWG) void k_softmax_xent(int64_t n, int c, const float *__restrict__ Zin,
                                                       const float *__restrict__ bias,
                                                       const int32_t *__restrict__ labels,
@@ -69,20 +71,55 @@ __global__ __launch_bounds__(kWG) void k_softmax_xent(int64_t n, int c, const fl
 {
     const int64_t r = (int64_t)blockIdx.x * kWG + threadIdx.x;
     if (r >= n) return;
-    const float *z = Zin + r * c;
-    float m = -INFINITY;
-    for (int j = 0; j < c; ++j) m = fmaxf(m, z[j] + bias[j]);
-    float s = 0.f;
-    for (int j = 0; j < c; ++j) s += expf(z[j] + bias[j] - m);
     const int y = labels[r];
-    const float inv = 1.f / s, invn = 1.f / (float)n;
-    for (int j = 0; j < c; ++j) {
-        const float zj = z[j] + bias[j];
-        const float p = expf(zj - m) * inv;
-        dZ[r * c + j] = (p - (j == y ? 1.f : 0.f)) * invn;
-        if (Zout) Zout[r * c + j] = zj;
+    const float invn = 1.f / (float)n;
+    if constexpr (CMAX > 0) {
+        float z[CMAX];
+#pragma unroll
+        for (int j = 0; j < CMAX; j += 4) {
+            if (j < c) {
+                const float4 t = *reinterpret_cast<const float4 *>(Zin + r * c + j);
+                const float4 bb = *reinterpret_cast<const float4 *>(bias + j);
+                z[j] = t.x + bb.x; z[j + 1] = t.y + bb.y; z[j + 2] = t.z + bb.z; z[j + 3] = t.w + bb.w;
+            }
+        }
+        float m = -INFINITY, zy = 0.f;
+#pragma unroll
+        for (int j = 0; j < CMAX; ++j)
+            if (j < c) { m = fmaxf(m, z[j]); zy = (j == y) ? z[j] : zy; }
+        float s = 0.f, e[CMAX];
+#pragma unroll
+        for (int j = 0; j < CMAX; ++j)
+            if (j < c) { e[j] = expf(z[j] - m); s += e[j]; }
+        const float inv = 1.f / s;
+#pragma unroll
+        for (int j = 0; j < CMAX; j += 4) {
+            if (j < c) {
+                float4 d;
+                d.x = (e[j] * inv - (j == y ? 1.f : 0.f)) * invn;
+                d.y = (e[j + 1] * inv - (j + 1 == y ? 1.f : 0.f)) * invn;
+                d.z = (e[j + 2] * inv - (j + 2 == y ? 1.f : 0.f)) * invn;
+                d.w = (e[j + 3] * inv - (j + 3 == y ? 1.f : 0.f)) * invn;
+                *reinterpret_cast<float4 *>(dZ + r * c + j) = d;
+                if (Zout) *reinterpret_cast<float4 *>(Zout + r * c + j) = make_float4(z[j], z[j + 1], z[j + 2], z[j + 3]);
+            }
+        }
+        rowloss[r] = (logf(s) + m - zy) * invn;
+    } else {
+        const float *z = Zin + r * c;
+        float m = -INFINITY;
+        for (int j = 0; j < c; ++j) m = fmaxf(m, z[j] + bias[j]);
+        float s = 0.f;
+        for (int j = 0; j < c; ++j) s += expf(z[j] + bias[j] - m);
+        const float inv = 1.f / s;
+        for (int j = 0; j < c; ++j) {
+            const float zj = z[j] + bias[j];
+            const float p = expf(zj - m) * inv;
+            dZ[r * c + j] = (p - (j == y ? 1.f : 0.f)) * invn;
+            if (Zout) Zout[r * c + j] = zj;
+        }
+        rowloss[r] = (logf(s) + m - (z[y] + bias[y])) * invn;
     }
-    rowloss[r] = (logf(s) + m - (z[y] + bias[y])) * invn;
 }
 
 // stage 1: chunk q sums rows [q*rows_per, ...) column-wise into part[q][f]
@@ -180,8 +217,15 @@ int launch_softmax_xent(int64_t n, int32_t c, const float *Zin, const float *bia
                         const int32_t *labels, float *Zout, float *dZ, float *rowloss, void *stream)
 {
     if (n == 0) return AG_OK;
-    hipLaunchKernelGGL(k_softmax_xent, grid1(n), dim3(kWG), 0, (hipStream_t)stream, n, c, Zin, bias,
-                       labels, Zout, dZ, rowloss);
+    if (c % 4 == 0 && c <= 16)
+        hipLaunchKernelGGL((k_softmax_xent<16>), grid1(n), dim3(kWG), 0, (hipStream_t)stream, n, c, Zin, bias,
+                           labels, Zout, dZ, rowloss);
+    else if (c % 4 == 0 && c <= 64)
+        hipLaunchKernelGGL((k_softmax_xent<64>), grid1(n), dim3(kWG), 0, (hipStream_t)stream, n, c, Zin, bias,
+                           labels, Zout, dZ, rowloss);
+    else
+        hipLaunchKernelGGL((k_softmax_xent<0>), grid1(n), dim3(kWG), 0, (hipStream_t)stream, n, c, Zin, bias,
+                           labels, Zout, dZ, rowloss);
     return hip_fail((int)hipGetLastError(), "softmax_xent launch");
 }
 

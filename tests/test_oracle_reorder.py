@@ -171,3 +171,18 @@ def test_permutation_invariance_of_aggregation():
     Yp = (oracle.spmm(s.intra_rowptr, s.intra_col, s.intra_val, Hp, want_abs=False)
           + oracle.spmm(s.inter_rowptr, s.inter_col, s.inter_val, Hp, want_abs=False))
     np.testing.assert_allclose(Yp[r.iperm], Y, rtol=1e-12, atol=1e-14)
+
+
+def test_golden_trace_fixture():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "reorder_traces.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, n, edges, cap, minb, comm, blk, perm = [x.strip() for x in line.split("|")]
+        e = [tuple(map(int, p.split("-"))) for p in edges.split()]
+        g = from_edges(int(n), [a for a, _ in e], [b for _, b in e])
+        r = ro(g, block_cap=int(cap), min_block=int(minb))
+        assert r.comm.tolist() == list(map(int, comm.split())), name
+        assert r.blk_ptr.tolist() == list(map(int, blk.split())), name
+        assert r.perm.tolist() == list(map(int, perm.split())), name
