@@ -1,0 +1,96 @@
+"""More GPU parity cases: paper-faithful community size, odd widths on every kernel family, plans
+without blocks, a non-default stream, interleaved plans, single-vertex graphs."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2305_17408_amd as ag
+from ag_inputs import (config_graph, planted_partition, gcn_normalise, mixed_density, from_edges,
+                       directed_random, features)
+from gpu_util import Case, COMBOS, check, force, say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_community_size_16_as_in_the_paper():
+    g = gcn_normalise(planted_partition(200, 16, 6, 0.8, 71))
+    c = Case(g, 32, block_cap=16, min_block=4)
+    st = ag.ag_plan_stats(c.plan)
+    assert st["n_blocks"] > 150 and st["density_intra"] > 0.2
+    c.check_all_combos()
+    c.close()
+
+
+@pytest.mark.parametrize("F", [3, 36, 100, 132, 512])
+def test_odd_widths_with_dense_class_blocks(F):
+    g = mixed_density(5, 128, 0.35, 5, 0.03, 73)
+    c = Case(g, F, seed=F)
+    assert ag.ag_plan_stats(c.plan)["n_dense_blocks"] >= 4
+    c.check_all_combos(directions=(0,))
+    gw = gcn_normalise(g)
+    c2 = Case(gw, F, seed=F + 1)
+    c2.check_all_combos(combos=["split_dense_narrow", "fused_narrow"], directions=(0,))
+    c.close()
+    c2.close()
+
+
+def test_no_blocks_at_all_and_tiny_graphs():
+    # uniform sparse graph with a high min_block: every vertex lands in the tail
+    g = directed_random(4000, 3.0, 79)
+    c = Case(g, 24, min_block=129)        # larger than any community can get
+    assert ag.ag_plan_stats(c.plan)["n_blocks"] == 0
+    c.check_all_combos()
+    # adaptive on a block-less plan
+    p = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, 24, min_block=129)
+    import torch
+    x = torch.from_numpy(c.H).cuda()
+    y = torch.empty_like(x)
+    for _ in range(30):
+        ag.ag_aggregate(p, x, y)
+    torch.cuda.synchronize()
+    check(y, c.Yref, c.Sy, "adaptive, no blocks")
+    assert ag.ag_plan_selector_info(p, 0)["frozen"]
+    ag.ag_plan_destroy(p)
+    c.close()
+    for n in (1, 2, 17):
+        g = gcn_normalise(from_edges(n, np.arange(n - 1), np.arange(1, n)))
+        c = Case(g, 8, min_block=1)
+        c.check_all_combos()
+        c.close()
+
+
+def test_non_default_stream_and_interleaved_plans():
+    import torch
+    g1 = config_graph(0)
+    g2 = gcn_normalise(mixed_density(4, 128, 0.3, 6, 0.02, 83))
+    c1, c2 = Case(g1, 16), Case(g2, 48)
+    s = torch.cuda.Stream()
+    x1, x2 = torch.from_numpy(c1.H).cuda(), torch.from_numpy(c2.H).cuda()
+    y1, y2 = torch.empty_like(x1), torch.empty_like(x2)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        for _ in range(25):                       # through the trials of both plans, interleaved
+            ag.ag_aggregate(c1.plan, x1, y1, stream=s)
+            ag.ag_aggregate(c2.plan, x2, y2, stream=s)
+    s.synchronize()
+    check(y1, c1.Yref, c1.Sy, "plan 1 on side stream")
+    check(y2, c2.Yref, c2.Sy, "plan 2 on side stream")
+    c1.close()
+    c2.close()
+
+
+def test_profiling_api_reports_calls():
+    import torch
+    c = Case(config_graph(1, scale=1 / 8), 64)
+    force(c.plan, "fused_narrow", 0)
+    ag.ag_plan_set_profiling(c.plan, True)
+    x = torch.from_numpy(c.H).cuda()
+    y = torch.empty_like(x)
+    for _ in range(70):                           # more than the event ring holds
+        ag.ag_aggregate(c.plan, x, y)
+    prof = ag.ag_plan_profile(c.plan, 0)
+    assert prof["calls"] == 70 and prof["total_ms"] > 0 and prof["compose"] == ag.AG_COMPOSE_FUSED
+    assert prof["class_ms"][0] > 0
+    ag.ag_plan_set_profiling(c.plan, False)
+    check(y, c.Yref, c.Sy, "profiled calls")
+    c.close()
