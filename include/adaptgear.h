@@ -184,6 +184,7 @@ typedef struct {
     double  density_full, density_intra, density_inter;  /* cf. the paper's density figure   */
     double  sec_reorder, sec_split, sec_build, sec_upload;
     int64_t device_bytes;                      /* topology held on the device                */
+    int32_t block_density_hist[8];             /* diagonal blocks with density in [k/8, (k+1)/8) */
 } ag_stats;
 
 int ag_plan_stats(const ag_plan *p, ag_stats *out);

@@ -63,7 +63,8 @@ class ag_stats(C.Structure):
                 ("n_long_rows", C.c_int64), ("n_long_segments", C.c_int64),
                 ("density_full", C.c_double), ("density_intra", C.c_double), ("density_inter", C.c_double),
                 ("sec_reorder", C.c_double), ("sec_split", C.c_double), ("sec_build", C.c_double),
-                ("sec_upload", C.c_double), ("device_bytes", C.c_int64)]
+                ("sec_upload", C.c_double), ("device_bytes", C.c_int64),
+                ("block_density_hist", C.c_int32 * 8)]
 
 
 class ag_profile(C.Structure):
@@ -228,7 +229,9 @@ def ag_plan_export(plan) -> dict:
 def ag_plan_stats(plan) -> dict:
     s = ag_stats()
     _check(lib().ag_plan_stats(plan, C.byref(s)))
-    return {k: getattr(s, k) for k, _ in ag_stats._fields_}
+    d = {k: getattr(s, k) for k, _ in ag_stats._fields_}
+    d["block_density_hist"] = list(s.block_density_hist)
+    return d
 
 
 def ag_plan_set_profiling(plan, on: bool) -> None:

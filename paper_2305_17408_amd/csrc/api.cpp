@@ -674,9 +674,12 @@ int ag_plan_stats(const ag_plan *p, ag_stats *out)
     out->n_long_segments = (int64_t)t.h[0].segs_inter.seg_row.size();
     const double nn = (double)t.n * (double)t.n;
     double blk_area = 0;
+    const HostCsr &I = t.h[0].intra;
     for (int32_t b = 0; b < t.r.n_blocks; ++b) {
-        const double s = t.r.blk_ptr[b + 1] - t.r.blk_ptr[b];
+        const int32_t r0 = t.r.blk_ptr[b], r1 = t.r.blk_ptr[b + 1];
+        const double s = r1 - r0, d = (I.rowptr[r1] - I.rowptr[r0]) / (s * s);
         blk_area += s * s;
+        out->block_density_hist[std::min(7, (int)(d * 8.0))]++;
     }
     out->density_full = nn > 0 ? (double)t.nnz / nn : 0;
     out->density_intra = blk_area > 0 ? (double)out->nnz_intra / blk_area : 0;

@@ -14,6 +14,8 @@
 // pointers of the team's rows sit in its lanes.  The kernel is bound by vector-ALU issue, not
 // by LDS or HBM, which is why a lane carries NV = 2 vectors for wide features (half the
 // shuffles and address arithmetic per FMA).
+#include <atomic>
+
 #include "kernels_common.h"
 
 namespace ag {
@@ -198,15 +200,18 @@ int launch_one(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev 
 {
     constexpr int FT = G * VEC * NV;
     constexpr size_t lds = (size_t)(kMaxBlock + 1) * FT * sizeof(float);
-    static bool prepared = false;                       // per instantiation
-    if (!prepared) {
-        if (lds > 65536) {
+    if (lds > 65536) {
+        // more than the default 64 KB of dynamic LDS has to be requested once per device
+        static std::atomic<bool> prepared[64];          // per instantiation and device
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        if (dev < 0 || dev >= 64 || !prepared[dev].load(std::memory_order_acquire)) {
             int rc = hip_fail((int)hipFuncSetAttribute((const void *)k_block_sparse<G, NV, VEC, FUSED>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
                               "LDS size attribute");
             if (rc) return rc;
+            if (dev >= 0 && dev < 64) prepared[dev].store(true, std::memory_order_release);
         }
-        prepared = true;
     }
     dim3 grid(nlist, (F + FT - 1) / FT);
     hipLaunchKernelGGL((k_block_sparse<G, NV, VEC, FUSED>), grid, dim3(kWG), lds, st, B, list, R, H, Y, F);

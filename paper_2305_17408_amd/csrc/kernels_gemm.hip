@@ -16,7 +16,7 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kKS = 16;            // K rows staged per step
+constexpr int kKSdef = 16;         // K rows staged per step
 constexpr int kMaxChunks = 512;    // K-splits (partials) per output tile
 
 // load 4 consecutive floats of row `r` starting at column c (zero beyond `cols` / `rows`)
@@ -35,7 +35,7 @@ __device__ __forceinline__ float4 guarded_load4(const float *__restrict__ M, int
 }
 
 // WAVES_M x WAVES_N wavefronts (= 4), each owning WM x WN tiles of 32 x 32.
-template <int WAVES_M, int WAVES_N, int WM, int WN>
+template <int WAVES_M, int WAVES_N, int WM, int WN, int kKS>
 __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, const float *__restrict__ B,
                                                  float *__restrict__ part, int64_t K, int m, int n,
                                                  int64_t rows_per_chunk, float *__restrict__ colsum_part)
@@ -64,7 +64,24 @@ __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, co
 #pragma unroll
     for (int u = 0; u < UB; ++u) cs[u] = make_float4(0.f, 0.f, 0.f, 0.f);
     const bool want_cs = colsum_part != nullptr && blockIdx.y == 0;
-    auto fetch = [&](int64_t k0) {
+    // interior tiles (all columns present, 16-byte aligned rows) take unguarded 16-byte loads
+    const bool interior = va && vb && m0 + TM <= m && n0 + TN <= n;
+    auto fetch_fast = [&](int64_t k0) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * kWG, r = idx / (TM / 4), c = (idx % (TM / 4)) * 4;
+            if (idx < NA) ra[u] = *reinterpret_cast<const float4 *>(A + (k0 + r) * m + m0 + c);
+        }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int idx = tid + u * kWG, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
+            if (idx < NB) {
+                rb[u] = *reinterpret_cast<const float4 *>(B + (k0 + r) * n + n0 + c);
+                cs[u].x += rb[u].x; cs[u].y += rb[u].y; cs[u].z += rb[u].z; cs[u].w += rb[u].w;
+            }
+        }
+    };
+    auto fetch_safe = [&](int64_t k0) {
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
             const int idx = tid + u * kWG, r = idx / (TM / 4), c = (idx % (TM / 4)) * 4;
@@ -92,6 +109,10 @@ __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, co
         }
     };
 
+    auto fetch = [&](int64_t k0) {
+        if (interior && k0 + kKS <= k_end) fetch_fast(k0);
+        else fetch_safe(k0);
+    };
     if (k_begin < k_end) {
         fetch(k_begin);
         stash(0);
@@ -202,7 +223,20 @@ __global__ __launch_bounds__(kWG, 2) void k_gemm_nn(const float *__restrict__ A,
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     float4 ra[UA], rw[UW];
-    auto fetch = [&](int k0) {
+    const bool interior = va && vw && r0 + TM <= N && n0 + TN <= n;
+    auto fetch_fast = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * kWG, r = idx / (kNK / 4), c = (idx % (kNK / 4)) * 4;
+            if (idx < NA) ra[u] = *reinterpret_cast<const float4 *>(A + (r0 + r) * k + k0 + c);
+        }
+#pragma unroll
+        for (int u = 0; u < UW; ++u) {
+            const int idx = tid + u * kWG, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
+            if (idx < NW) rw[u] = *reinterpret_cast<const float4 *>(W + (size_t)(k0 + r) * n + n0 + c);
+        }
+    };
+    auto fetch_safe = [&](int k0) {
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
             const int idx = tid + u * kWG, r = idx / (kNK / 4), c = (idx % (kNK / 4)) * 4;
@@ -230,6 +264,10 @@ __global__ __launch_bounds__(kWG, 2) void k_gemm_nn(const float *__restrict__ A,
         }
     };
 
+    auto fetch = [&](int k0) {
+        if (interior && k0 + kNK <= k) fetch_fast(k0);
+        else fetch_safe(k0);
+    };
     fetch(0);
     for (int k0 = 0; k0 < k; k0 += kNK) {
         __syncthreads();                       // everyone is done reading the previous tiles
@@ -380,16 +418,17 @@ int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float 
         return launch_fill_zero((int64_t)m * n, C, stream);
     }
     float *cs_part = colsum ? scratch + (size_t)kMaxChunks * m * n : nullptr;
+    const int kKS = kKSdef;
     int64_t steps = (K + kKS - 1) / kKS;
     int nchunks = (int)std::max<int64_t>(1, std::min<int64_t>(kMaxChunks, steps));
     int64_t rows_per_chunk = ((steps + nchunks - 1) / nchunks) * kKS;
     nchunks = (int)std::max<int64_t>(1, (K + rows_per_chunk - 1) / rows_per_chunk);
     if (n > 32) {
         dim3 grid(nchunks, (m + 127) / 128, (n + 255) / 256);
-        hipLaunchKernelGGL((k_gemm_tn<2, 2, 2, 4>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
+        hipLaunchKernelGGL((k_gemm_tn<2, 2, 2, 4, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     } else {
         dim3 grid(nchunks, (m + 255) / 256, 1);
-        hipLaunchKernelGGL((k_gemm_tn<4, 1, 2, 1>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
+        hipLaunchKernelGGL((k_gemm_tn<4, 1, 2, 1, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     }
     const int64_t count = (int64_t)m * n;
     hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 31) / 32)), dim3(kWG), 0, st, nchunks,

@@ -80,6 +80,7 @@ def test_dense_blocks_are_classified():
     st = ag.ag_plan_stats(p)
     ag.ag_plan_destroy(p)
     assert 6 <= st["n_dense_blocks"] <= 9
+    assert sum(st["block_density_hist"]) == st["n_blocks"] and sum(st["block_density_hist"][2:]) >= 6
     assert 0.1 < st["density_intra"] < 0.35
 
 
