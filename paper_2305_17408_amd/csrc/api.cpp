@@ -3,6 +3,7 @@
 
 #include <algorithm>
 #include <chrono>
+#include <cstdint>
 #include <cstring>
 
 #include "ag_internal.h"
@@ -403,6 +404,10 @@ int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
     if (t.n == 0) return AG_OK;
     if (!X || !Y) { set_error("null argument"); return AG_ERR_INVALID; }
     if (X == Y) { set_error("input and output must not alias"); return AG_ERR_INVALID; }
+    if (p->F % 4 == 0 && (((uintptr_t)X | (uintptr_t)Y) & 15)) {
+        set_error("feature matrices must be 16-byte aligned");
+        return AG_ERR_INVALID;
+    }
     hipStream_t st = (hipStream_t)stream;
     const int dir_idx = (dir == AG_DIR_BWD && !t.symmetric) ? 1 : 0;
     Selector &s = p->sel[dir];
@@ -567,6 +572,10 @@ int ag_permute_rows(const ag_plan *p, const float *src, float *dst, int32_t F, i
 {
     if (!p || !src || !dst || F < 1 || src == dst) { set_error("bad argument"); return AG_ERR_INVALID; }
     if (p->topo->host_only) { set_error("host-only plan"); return AG_ERR_UNSUPPORTED; }
+    if (F % 4 == 0 && (((uintptr_t)src | (uintptr_t)dst) & 15)) {
+        set_error("feature matrices must be 16-byte aligned");
+        return AG_ERR_INVALID;
+    }
     return launch_permute_rows(p->topo->perm_dev, p->topo->n, F, src, dst, inverse != 0, stream);
 }
 

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdint>
 
 #include "ag_internal.h"
 
@@ -24,9 +25,13 @@ struct Ws {
     float *P, *H1, *Q, *Z, *dZ, *dQ, *dH1, *rowloss, *W2T, *scratch;
 };
 
+// every sub-buffer starts on a 16-byte boundary (the kernels use 16-byte loads where widths allow)
+size_t pad4(size_t floats) { return (floats + 3) & ~(size_t)3; }
+
 size_t ws_floats(int64_t n, int32_t fi, int32_t hd, int32_t c)
 {
-    return (size_t)n * ((size_t)fi + 2 * (size_t)hd + 4 * (size_t)c + 1) + (size_t)hd * c +
+    return pad4((size_t)n * fi) + 2 * pad4((size_t)n * hd) + 4 * pad4((size_t)n * c) + pad4((size_t)n) +
+           pad4((size_t)hd * c) +
            std::max(col_sum_scratch_floats(std::max(hd, c)),
                     std::max(gemm_tn_scratch_floats(fi, hd), gemm_tn_scratch_floats(hd, c))) + 64;
 }
@@ -61,17 +66,21 @@ int ag_gcn_step(ag_plan *p_in, ag_plan *p_out, const ag_gcn_io *io, const float 
         return AG_ERR_INVALID;
     }
     if (workspace_bytes < ag_gcn_workspace_bytes(n, fi, hd, c)) { set_error("workspace too small"); return AG_ERR_INVALID; }
+    const uintptr_t align_all = (uintptr_t)X | (uintptr_t)workspace | (uintptr_t)io->W1 | (uintptr_t)io->b1 |
+                                (uintptr_t)io->W2 | (uintptr_t)io->b2 | (uintptr_t)io->dW1 | (uintptr_t)io->dW2 |
+                                (uintptr_t)io->logits;
+    if (align_all & 15) { set_error("device pointers must be 16-byte aligned"); return AG_ERR_INVALID; }
     Ws w;
     float *q = (float *)workspace;
-    w.P = q; q += (size_t)n * fi;
-    w.H1 = q; q += (size_t)n * hd;
-    w.dH1 = q; q += (size_t)n * hd;
-    w.Q = q; q += (size_t)n * c;
-    w.Z = q; q += (size_t)n * c;
-    w.dZ = q; q += (size_t)n * c;
-    w.dQ = q; q += (size_t)n * c;
-    w.rowloss = q; q += (size_t)n;
-    w.W2T = q; q += (size_t)hd * c;
+    w.P = q; q += pad4((size_t)n * fi);
+    w.H1 = q; q += pad4((size_t)n * hd);
+    w.dH1 = q; q += pad4((size_t)n * hd);
+    w.Q = q; q += pad4((size_t)n * c);
+    w.Z = q; q += pad4((size_t)n * c);
+    w.dZ = q; q += pad4((size_t)n * c);
+    w.dQ = q; q += pad4((size_t)n * c);
+    w.rowloss = q; q += pad4((size_t)n);
+    w.W2T = q; q += pad4((size_t)hd * c);
     w.scratch = q;
     int rc;
     // forward

@@ -118,7 +118,8 @@ __global__ __launch_bounds__(kWG) void k_softmax_xent(int64_t n, int c, const fl
             dZ[r * c + j] = (p - (j == y ? 1.f : 0.f)) * invn;
             if (Zout) Zout[r * c + j] = zj;
         }
-        rowloss[r] = (logf(s) + m - (z[y] + bias[y])) * invn;
+        const float zy = (y >= 0 && y < c) ? z[y] + bias[y] : 0.f;      // a label outside [0,c) reads nothing
+        rowloss[r] = (logf(s) + m - zy) * invn;
     }
 }
 

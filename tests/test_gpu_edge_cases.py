@@ -94,3 +94,24 @@ def test_profiling_api_reports_calls():
     ag.ag_plan_set_profiling(c.plan, False)
     check(y, c.Yref, c.Sy, "profiled calls")
     c.close()
+
+
+def test_misaligned_feature_pointer_is_rejected():
+    import torch
+    c = Case(config_graph(0), 16)
+    buf = torch.zeros(c.g.n * 16 + 4, device="cuda")
+    x = buf[1:1 + c.g.n * 16].view(c.g.n, 16)          # 4-byte aligned only
+    y = torch.empty(c.g.n, 16, device="cuda")
+    with pytest.raises(ag.AdaptGearError) as ei:
+        ag.ag_aggregate(c.plan, x, y)
+    assert ei.value.code == ag.AG_ERR_INVALID
+    c.close()
+
+
+def test_gcn_step_with_widths_that_are_not_multiples_of_four():
+    from test_gpu_gcn import run_step, compare
+    g = gcn_normalise(planted_partition(6, 50, 6, 0.7, 91))      # n = 300
+    got, ref, perm = run_step(g, 10, 7, 3)
+    compare(got, ref, perm)
+    got, ref, perm = run_step(g, 12, 5, 8)
+    compare(got, ref, perm)
