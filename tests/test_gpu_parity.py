@@ -105,6 +105,17 @@ def test_exact_cases():
     c.close()
 
 
+def test_symmetric_matrix_backward_is_the_forward_kernel():
+    c = Case(config_graph(0), 16)
+    assert ag.ag_plan_stats(c.plan)["symmetric"] == 1
+    for name in DETERMINISTIC:
+        force(c.plan, name, 0)
+        force(c.plan, name, 1)
+        c.G = c.H                                   # same input both ways
+        assert np.array_equal(c.forward().cpu().numpy(), c.backward().cpu().numpy()), name
+    c.close()
+
+
 def test_runs_are_bitwise_reproducible():
     g = config_graph(2, scale=1 / 32)
     c = Case(g, 64)

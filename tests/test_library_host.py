@@ -126,3 +126,38 @@ def test_input_validation():
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_force_kernels(p, 7, 0, 0))
     ag.ag_plan_force_kernels(p, ag.AG_CLS_COMPOSE, ag.AG_DIR_FWD, ag.AG_COMPOSE_FUSED)
     ag.ag_plan_destroy(p)
+
+
+def test_failing_allocator_callback_gives_nomem_without_touching_the_gpu():
+    import ctypes as C
+    calls = []
+    ALLOC = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+    FREE = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+    def alloc(nbytes, user):
+        calls.append(nbytes)
+        return None                                   # always out of memory
+
+    def free(ptr, user):
+        calls.append(-1)
+
+    a, f = ALLOC(alloc), FREE(free)
+    g = planted_partition(2, 16, 4, 0.7, 1)
+    expect_error(ag.AG_ERR_NOMEM, lambda: ag.ag_plan_create(
+        g.rowptr, g.colidx, None, g.n, 4, dev_alloc=C.cast(a, C.c_void_p), dev_free=C.cast(f, C.c_void_p)))
+    assert calls and calls[0] > 0 and -1 not in calls
+    # only one of the two callbacks given is an error
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(
+        g.rowptr, g.colidx, None, g.n, 4, dev_alloc=C.cast(a, C.c_void_p)))
+
+
+def test_null_and_mismatched_arguments_to_the_drivers():
+    g = planted_partition(2, 16, 4, 0.7, 1)
+    p = host_plan(g, F=4)
+    L = ag.lib()
+    assert L.ag_aggregate(p, None, None, None) == ag.AG_ERR_UNSUPPORTED      # host-only plan
+    assert L.ag_aggregate(None, None, None, None) == ag.AG_ERR_INVALID
+    assert L.ag_plan_stats(None, None) == ag.AG_ERR_INVALID
+    assert ag.ag_gcn_workspace_bytes(100, 8, 0, 4) == 0
+    assert ag.ag_gcn_workspace_bytes(100, 8, 16, 4) >= 4 * 100 * (8 + 2 * 16 + 4 * 4 + 1)
+    ag.ag_plan_destroy(p)
