@@ -117,10 +117,8 @@ int launch_block_dense(const BlocksDev &B, const float *H, float *Y, int32_t F, 
 int launch_permute_rows(const int32_t *perm, int64_t n, int32_t F, const float *src, float *dst,
                         bool inverse, void *stream);
 int launch_axpy(int64_t count, float a, const float *x, float *y, void *stream);
-int launch_bias_relu(int64_t n, int32_t f, const float *bias, float *M, void *stream);
 int launch_softmax_xent(int64_t n, int32_t c, const float *Zin, const float *bias,
                         const int32_t *labels, float *Zout, float *dZ, float *rowloss, void *stream);
-int launch_relu_grad(int64_t count, const float *act, float *grad, void *stream);
 size_t col_sum_scratch_floats(int32_t f);
 int launch_col_sum(int64_t n, int32_t f, const float *M, float *out, float *scratch, void *stream);
 int launch_fill_zero(int64_t count, float *p, void *stream);

@@ -43,22 +43,6 @@ __global__ __launch_bounds__(kWG) void k_fill_zero(int64_t count, float *__restr
     if (i < count) p[i] = 0.f;
 }
 
-// M[r][c] = max(M[r][c] + bias[c], 0)
-__global__ __launch_bounds__(kWG) void k_bias_relu(int64_t count, int f, const float *__restrict__ bias,
-                                                   float *__restrict__ M)
-{
-    const int64_t i = (int64_t)blockIdx.x * kWG + threadIdx.x;
-    if (i < count) M[i] = fmaxf(M[i] + bias[i % f], 0.f);
-}
-
-// grad[i] = act[i] > 0 ? grad[i] : 0
-__global__ __launch_bounds__(kWG) void k_relu_grad(int64_t count, const float *__restrict__ act,
-                                                   float *__restrict__ grad)
-{
-    const int64_t i = (int64_t)blockIdx.x * kWG + threadIdx.x;
-    if (i < count && !(act[i] > 0.f)) grad[i] = 0.f;
-}
-
 // One thread per vertex: z = Zin + bias; row loss = logsumexp(z) - z[label] (max-subtracted);
 // dZ = (softmax(z) - onehot) / n.  Zout (optional) receives z.  CMAX > 0: the row (c <= CMAX,
 // c % 4 == 0) is held in registers and moved with 16-byte loads and stores.
@@ -198,20 +182,6 @@ int launch_fill_zero(int64_t count, float *p, void *stream)
     if (count == 0) return AG_OK;
     hipLaunchKernelGGL(k_fill_zero, grid1(count), dim3(kWG), 0, (hipStream_t)stream, count, p);
     return hip_fail((int)hipGetLastError(), "fill launch");
-}
-
-int launch_bias_relu(int64_t n, int32_t f, const float *bias, float *M, void *stream)
-{
-    if (n == 0) return AG_OK;
-    hipLaunchKernelGGL(k_bias_relu, grid1(n * f), dim3(kWG), 0, (hipStream_t)stream, n * f, f, bias, M);
-    return hip_fail((int)hipGetLastError(), "bias_relu launch");
-}
-
-int launch_relu_grad(int64_t count, const float *act, float *grad, void *stream)
-{
-    if (count == 0) return AG_OK;
-    hipLaunchKernelGGL(k_relu_grad, grid1(count), dim3(kWG), 0, (hipStream_t)stream, count, act, grad);
-    return hip_fail((int)hipGetLastError(), "relu_grad launch");
 }
 
 int launch_softmax_xent(int64_t n, int32_t c, const float *Zin, const float *bias,
