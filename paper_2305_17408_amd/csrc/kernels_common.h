@@ -71,13 +71,13 @@ __device__ __forceinline__ void stage_tile(const float *__restrict__ H, int F, i
 // One chunk of a CSR row held in registers: lane tl of the team holds entry tl's column `c` and
 // value `v` (cnt <= W entries are valid).  The W/G lane groups (G lanes, each lane owning VEC
 // features starting at column f) pass the entries round with lane shuffles and gather the
-// feature rows of their share from global memory, 4 independent loads in flight per lane.
+// feature rows of their share from global memory, 8 independent loads in flight per lane.
 // All W lanes of the team must call this together.
 template <int G, int W, int VEC>
 __device__ __forceinline__ void team_chunk_gather(int c, float v, int cnt, const float *__restrict__ H,
                                                   int F, int f, bool fok, int tl, float (&acc)[VEC])
 {
-    constexpr int NSG = W / G, U = 4;
+    constexpr int NSG = W / G, U = 8;
     const int sg = tl / G;
     for (int k0 = 0; k0 < cnt; k0 += NSG * U) {
         int ck[U];
