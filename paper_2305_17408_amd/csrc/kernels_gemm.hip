@@ -384,6 +384,93 @@ __global__ __launch_bounds__(kWG) void k_gemm_nn_smallk(const float *__restrict_
     }
 }
 
+// Backward through the second GCN layer's transform in one pass over H1 and dQ (both are read
+// once): dPre = (dQ W2^T) * (H1 > 0) is written, and the weight gradient dW2 = H1^T dQ is
+// accumulated on the way.  A thread owns 4 hidden columns; its slice of W2^T and its 4 x KMAX
+// piece of dW2 live in registers; one wavefront's rows are reduced by a second kernel from
+// per-wavefront partials (fixed order).  Bandwidth bound, vector ALUs only.
+template <int KMAX>
+__global__ __launch_bounds__(kWG) void k_hidden_backward(const float *__restrict__ dQ,
+                                                         const float *__restrict__ W2T,
+                                                         const float *__restrict__ H1, float *__restrict__ dPre,
+                                                         float *__restrict__ part, int64_t N, int c, int hd,
+                                                         int rows_per_wg)
+{
+    const int tpr = hd / 4;                              // threads per row (hd % 4 == 0, tpr <= kWG)
+    const int rows_at_once = kWG / tpr;
+    const int sub = threadIdx.x / tpr, col = (threadIdx.x % tpr) * 4;
+    const bool active = sub < rows_at_once;              // left-over threads only take part in the barrier
+    float4 wreg[KMAX], gw[KMAX];                         // W2^T slice; dW2[col..col+3][q] accumulators
+#pragma unroll
+    for (int q = 0; q < KMAX; ++q) {
+        wreg[q] = (q < c) ? *reinterpret_cast<const float4 *>(W2T + (size_t)q * hd + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+        gw[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    const int64_t rb = (int64_t)blockIdx.x * rows_per_wg, re = active ? min(N, rb + rows_per_wg) : rb;
+    const bool vq = (c % 4 == 0);
+    // software pipeline: the loads of the next row are in flight while the current row is computed
+    float4 h_n = make_float4(0.f, 0.f, 0.f, 0.f), a_n[KMAX / 4];
+    auto fetch = [&](int64_t row) {
+        if (row < re) h_n = *reinterpret_cast<const float4 *>(H1 + row * hd + col);
+#pragma unroll
+        for (int q4 = 0; q4 < KMAX; q4 += 4) a_n[q4 / 4] = guarded_load4(dQ, row, re, q4, c, vq);
+    };
+    fetch(rb + sub);
+    for (int64_t row = rb + sub; row < re; row += rows_at_once) {
+        const float4 h = h_n;
+        float a[KMAX];
+#pragma unroll
+        for (int q4 = 0; q4 < KMAX; q4 += 4) {
+            a[q4] = a_n[q4 / 4].x; a[q4 + 1] = a_n[q4 / 4].y; a[q4 + 2] = a_n[q4 / 4].z; a[q4 + 3] = a_n[q4 / 4].w;
+        }
+        fetch(row + rows_at_once);
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int q = 0; q < KMAX; ++q) {
+            acc.x = fmaf(a[q], wreg[q].x, acc.x); acc.y = fmaf(a[q], wreg[q].y, acc.y);
+            acc.z = fmaf(a[q], wreg[q].z, acc.z); acc.w = fmaf(a[q], wreg[q].w, acc.w);
+            gw[q].x = fmaf(h.x, a[q], gw[q].x); gw[q].y = fmaf(h.y, a[q], gw[q].y);
+            gw[q].z = fmaf(h.z, a[q], gw[q].z); gw[q].w = fmaf(h.w, a[q], gw[q].w);
+        }
+        acc.x = h.x > 0.f ? acc.x : 0.f; acc.y = h.y > 0.f ? acc.y : 0.f;
+        acc.z = h.z > 0.f ? acc.z : 0.f; acc.w = h.w > 0.f ? acc.w : 0.f;
+        *reinterpret_cast<float4 *>(dPre + row * hd + col) = acc;
+    }
+    // the row groups of the work-group are combined through LDS (fixed order), then one partial
+    // dW2 per work-group goes out: part[wg][hd][c]
+    extern __shared__ float red[];                        // (rows_at_once - 1) x hd x KMAX floats
+    if (active && sub > 0) {
+        float *r = red + ((size_t)(sub - 1) * hd + col) * KMAX;
+#pragma unroll
+        for (int q = 0; q < KMAX; ++q) {
+            r[0 * KMAX + q] = gw[q].x; r[1 * KMAX + q] = gw[q].y;
+            r[2 * KMAX + q] = gw[q].z; r[3 * KMAX + q] = gw[q].w;
+        }
+    }
+    __syncthreads();
+    if (sub == 0) {
+        for (int g = 1; g < rows_at_once; ++g) {
+            const float *r = red + ((size_t)(g - 1) * hd + col) * KMAX;
+#pragma unroll
+            for (int q = 0; q < KMAX; ++q) {
+                gw[q].x += r[0 * KMAX + q]; gw[q].y += r[1 * KMAX + q];
+                gw[q].z += r[2 * KMAX + q]; gw[q].w += r[3 * KMAX + q];
+            }
+        }
+        float *o = part + (size_t)blockIdx.x * hd * c;
+#pragma unroll
+        for (int q = 0; q < KMAX; ++q)
+            if (q < c) {
+                o[(size_t)(col + 0) * c + q] = gw[q].x;
+                o[(size_t)(col + 1) * c + q] = gw[q].y;
+                o[(size_t)(col + 2) * c + q] = gw[q].z;
+                o[(size_t)(col + 3) * c + q] = gw[q].w;
+            }
+    }
+}
+
+constexpr int kHiddenRowsPerWg = 1024;
+
 template <int EPI>
 void run_nn(int64_t N, int k, int n, const float *A, const float *W, float *C, const float *aux, hipStream_t st)
 {
@@ -449,6 +536,33 @@ int launch_gemm_nn(int64_t N, int32_t k, int32_t n, const float *A, const float 
     else if (epilogue == EPI_RELU_MASK) run_nn<EPI_RELU_MASK>(N, k, n, A, W, C, aux, st);
     else run_nn<EPI_NONE>(N, k, n, A, W, C, aux, st);
     return hip_fail((int)hipGetLastError(), "gemm_nn launch");
+}
+
+// Fused dPre = (dQ W2T) * (H1 > 0) and dW2 = H1^T dQ for c <= 16 classes and hd % 4 == 0 (<= 1024);
+// returns AG_ERR_UNSUPPORTED for other shapes (the caller then uses the separate kernels).
+size_t hidden_backward_scratch_floats(int64_t N, int32_t hd, int32_t c)
+{
+    if (hd < 4 || hd % 4 || hd / 4 > kWG || c > 16) return 0;
+    const int64_t wgs = (N + kHiddenRowsPerWg - 1) / kHiddenRowsPerWg;
+    return (size_t)wgs * hd * c;
+}
+
+int launch_hidden_backward(int64_t N, int32_t hd, int32_t c, const float *dQ, const float *W2T, const float *H1,
+                           float *dPre, float *dW2, float *scratch, void *stream)
+{
+    if (hd < 4 || hd % 4 || hd / 4 > kWG || c > 16 || c < 1) return AG_ERR_UNSUPPORTED;
+    if ((size_t)(kWG / (hd / 4) - 1) * hd * 16 * sizeof(float) > 65536) return AG_ERR_UNSUPPORTED;   // LDS for the in-group sum
+    if (N <= 0) return launch_fill_zero((int64_t)hd * c, dW2, stream);
+    hipStream_t st = (hipStream_t)stream;
+    const int wgs = (int)((N + kHiddenRowsPerWg - 1) / kHiddenRowsPerWg);
+    const int groups = kWG / (hd / 4);
+    const size_t lds = (size_t)(groups - 1) * hd * 16 * sizeof(float);
+    hipLaunchKernelGGL((k_hidden_backward<16>), dim3(wgs), dim3(kWG), lds, st, dQ, W2T, H1, dPre, scratch, N, c, hd,
+                       kHiddenRowsPerWg);
+    const int64_t count = (int64_t)hd * c;
+    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 31) / 32)), dim3(kWG), 0, st, wgs, count,
+                       scratch, dW2);
+    return hip_fail((int)hipGetLastError(), "hidden_backward launch");
 }
 
 int launch_transpose_small(int32_t rows, int32_t cols, const float *in, float *out, void *stream)
