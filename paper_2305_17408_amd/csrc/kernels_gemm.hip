@@ -195,9 +195,9 @@ __global__ __launch_bounds__(kWG) void k_sum_partials(int nchunks, int64_t count
 // C[N x n] = epilogue(A[N x k] W[k x n])
 // ------------------------------------------------------------------------------------------
 enum { EPI_NONE = 0, EPI_BIAS_RELU = 1, EPI_RELU_MASK = 2 };
-constexpr int kNK = 16;             // k columns of A / rows of W staged per step
-
-template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
+// kNK = k columns of A / rows of W staged per step: 16 for the wide tile (register budget), 64 for
+// the narrow one (bandwidth-bound shape: whole 256-byte row pieces, fewer barriers)
+template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI, int kNK>
 __global__ __launch_bounds__(kWG, 2) void k_gemm_nn(const float *__restrict__ A, const float *__restrict__ W,
                                                  float *__restrict__ C, int64_t N, int k, int n,
                                                  const float *__restrict__ aux)
@@ -482,10 +482,10 @@ void run_nn(int64_t N, int k, int n, const float *A, const float *W, float *C, c
     }
     if (n > 32) {
         dim3 grid((unsigned)((N + 127) / 128), (n + 255) / 256);
-        hipLaunchKernelGGL((k_gemm_nn<2, 2, 2, 4, EPI>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
+        hipLaunchKernelGGL((k_gemm_nn<2, 2, 2, 4, EPI, 16>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
     } else {
         dim3 grid((unsigned)((N + 127) / 128), 1);
-        hipLaunchKernelGGL((k_gemm_nn<4, 1, 1, 1, EPI>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
+        hipLaunchKernelGGL((k_gemm_nn<4, 1, 1, 1, EPI, 64>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
     }
 }
 
