@@ -213,17 +213,18 @@ def ag_plan_export(plan) -> dict:
 
     def arr(p, count, dt):
         if not p or count == 0:
-            return np.empty(0, dt) if p or count == 0 else None
+            return np.empty(0, dt)
         return np.ctypeslib.as_array(p, shape=(count,)).astype(dt, copy=True)
 
     ni, no = int(e.nnz_intra), int(e.nnz_inter)
+    unit = bool(ag_plan_stats(plan)["unit_weights"])      # unit weights: no value arrays at all
     return dict(
         n=n, n_blocks=nb, perm=arr(e.perm, n, np.int32), iperm=arr(e.iperm, n, np.int32),
         blk_ptr=arr(e.blk_ptr, nb + 1, np.int32),
         intra_rowptr=arr(e.intra_rowptr, n + 1, np.int32), intra_col=arr(e.intra_col, ni, np.int32),
-        intra_val=arr(e.intra_val, ni, np.float32) if e.intra_val else None,
+        intra_val=None if unit else arr(e.intra_val, ni, np.float32),
         inter_rowptr=arr(e.inter_rowptr, n + 1, np.int32), inter_col=arr(e.inter_col, no, np.int32),
-        inter_val=arr(e.inter_val, no, np.float32) if e.inter_val else None)
+        inter_val=None if unit else arr(e.inter_val, no, np.float32))
 
 
 def ag_plan_stats(plan) -> dict:
