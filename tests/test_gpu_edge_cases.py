@@ -115,3 +115,43 @@ def test_gcn_step_with_widths_that_are_not_multiples_of_four():
     compare(got, ref, perm)
     got, ref, perm = run_step(g, 12, 5, 8)
     compare(got, ref, perm)
+
+
+def test_frozen_plan_can_be_captured_in_a_hip_graph():
+    """Once the selector is frozen a call only enqueues kernels (no allocation, no host wait), so it
+    can be recorded into a HIP graph; every replay must give the eager result."""
+    import torch
+    g = config_graph(1, scale=1 / 4)
+    c = Case(g, 64, layout=ag.AG_LAYOUT_REORDERED)
+    x = torch.from_numpy(c.H).cuda()
+    xp = torch.empty_like(x)
+    ag.ag_permute_rows(c.plan, x, xp, 64, False)
+    y = torch.empty_like(x)
+    d = torch.empty_like(x)
+    for combo in ("fused_narrow", "split_sparse_narrow", "full_csr_wide"):
+        force(c.plan, combo, 0)
+        force(c.plan, combo, 1)
+        ag.ag_aggregate(c.plan, xp, y)                      # eager warm-up (LDS attribute etc.)
+        ag.ag_aggregate_t(c.plan, xp, d)
+        torch.cuda.synchronize()
+        eager_y, eager_d = y.clone(), d.clone()
+        graph = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            with torch.cuda.graph(graph, stream=s):
+                ag.ag_aggregate(c.plan, xp, y, stream=s)
+                ag.ag_aggregate_t(c.plan, xp, d, stream=s)
+        torch.cuda.current_stream().wait_stream(s)
+        for rep in range(3):
+            y.fill_(float("nan"))
+            d.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y, eager_y) and torch.equal(d, eager_d), (combo, rep)
+        yo = torch.empty_like(y)
+        ag.ag_permute_rows(c.plan, y, yo, 64, True)
+        check(yo, c.Yref, c.Sy, f"graph replay {combo}")
+        del graph
+    c.close()
