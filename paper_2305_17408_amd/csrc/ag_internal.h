@@ -98,9 +98,10 @@ struct DevDir {
 
 // kernels_csr.hip
 // Rows [row_begin,row_end) of `A`: rows below `acc_below` add to Y, the others overwrite it.
-// `wide` selects several lane groups per row.  Long rows are left to launch_csr_long.
+// `variant` is the remainder kernel id (AG_K_CSR_WIDE; anything else = narrow).
+// Long rows are left to launch_csr_long.
 int launch_csr_rows(const CsrDev &A, const float *H, float *Y, int32_t F, int32_t row_begin,
-                    int32_t row_end, int32_t acc_below, bool wide, void *stream);
+                    int32_t row_end, int32_t acc_below, int variant, void *stream);
 // All long rows of `A`: segments -> partial[nseg][F] -> Y (rows below acc_below accumulate).
 int launch_csr_long(const CsrDev &A, const float *H, float *Y, int32_t F, float *partial,
                     int32_t acc_below, void *stream);

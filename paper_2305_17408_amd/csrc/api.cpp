@@ -232,7 +232,7 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
     const Topology &t = *p->topo;
     const DevDir &D = t.d[dir_idx];
     const int32_t F = p->F, n = (int32_t)t.n, nbr = D.blk.n_block_rows;
-    const bool wide = k[AG_CLS_REMAINDER] == AG_K_CSR_WIDE;
+    const int wide = k[AG_CLS_REMAINDER];                 // CSR kernel variant (COO falls back to narrow)
     const bool coo = k[AG_CLS_REMAINDER] == AG_K_COO;     // only the SPLIT composition has a COO form
     int rc = AG_OK;
     if (ev) (void)hipEventRecord(ev[0], st);

@@ -69,15 +69,16 @@ __device__ __forceinline__ void stage_tile(const float *__restrict__ H, int F, i
 }
 
 // One chunk of a CSR row held in registers: lane tl of the team holds entry tl's column `c` and
-// value `v` (cnt <= W entries are valid).  The W/G lane groups (G lanes, each lane owning VEC
-// features starting at column f) pass the entries round with lane shuffles and gather the
-// feature rows of their share from global memory, 8 independent loads in flight per lane.
-// All W lanes of the team must call this together.
-template <int G, int W, int VEC>
+// value `v` (cnt <= W entries are valid).  The W/G lane groups (G lanes, each lane owning NV
+// vectors of VEC features, vector q starting at column f + q*G*VEC) pass the entries round with
+// lane shuffles and gather the feature rows of their share from global memory, U*NV independent
+// loads in flight per lane.  All W lanes of the team must call this together.
+template <int G, int W, int NV, int VEC>
 __device__ __forceinline__ void team_chunk_gather(int c, float v, int cnt, const float *__restrict__ H,
-                                                  int F, int f, bool fok, int tl, float (&acc)[VEC])
+                                                  int F, int f, const bool (&fok)[NV], int tl,
+                                                  float (&acc)[NV][VEC])
 {
-    constexpr int NSG = W / G, U = 8;
+    constexpr int NSG = W / G, U = 8 / NV;
     const int sg = tl / G;
     for (int k0 = 0; k0 < cnt; k0 += NSG * U) {
         int ck[U];
@@ -88,31 +89,36 @@ __device__ __forceinline__ void team_chunk_gather(int c, float v, int cnt, const
             ck[u] = __shfl(c, kk & (W - 1), W);
             vk[u] = __shfl(v, kk & (W - 1), W);
         }
-        float h[U][VEC];
+        float h[U][NV][VEC];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int kk = k0 + u * NSG + sg;
-            if (kk < cnt && fok) {
-                load_vec<VEC>(H + (size_t)ck[u] * F + f, h[u]);
-            } else {
+            if (!(kk < cnt)) vk[u] = 0.f;
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) h[u][j] = 0.f;
-                vk[u] = 0.f;
+            for (int q = 0; q < NV; ++q) {
+                if (kk < cnt && fok[q]) {
+                    load_vec<VEC>(H + (size_t)ck[u] * F + f + q * G * VEC, h[u][q]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) h[u][q][j] = 0.f;
+                }
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[j] = fmaf(vk[u], h[u][j], acc[j]);
+            for (int q = 0; q < NV; ++q)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[q][j] = fmaf(vk[u], h[u][q][j], acc[q][j]);
     }
 }
 
 // Accumulate entries [beg,end) of one CSR row into acc, W entries per chunk (see above).
-template <int G, int W, int VEC>
+template <int G, int W, int NV, int VEC>
 __device__ __forceinline__ void team_row_gather(const int32_t *__restrict__ col,
                                                 const float *__restrict__ val, int beg, int end,
-                                                const float *__restrict__ H, int F, int f, bool fok,
-                                                int tl, float (&acc)[VEC])
+                                                const float *__restrict__ H, int F, int f,
+                                                const bool (&fok)[NV], int tl, float (&acc)[NV][VEC])
 {
     for (int base = beg; base < end; base += W) {
         const int e = base + tl;
@@ -122,18 +128,20 @@ __device__ __forceinline__ void team_row_gather(const int32_t *__restrict__ col,
             c = col[e];
             v = val ? val[e] : 1.f;
         }
-        team_chunk_gather<G, W, VEC>(c, v, min(W, end - base), H, F, f, fok, tl, acc);
+        team_chunk_gather<G, W, NV, VEC>(c, v, min(W, end - base), H, F, f, fok, tl, acc);
     }
 }
 
 // Sum the partial accumulators of the W/G lane groups of a team; every group ends with the total.
-template <int G, int W, int VEC>
-__device__ __forceinline__ void team_reduce(float (&acc)[VEC])
+template <int G, int W, int NV, int VEC>
+__device__ __forceinline__ void team_reduce(float (&acc)[NV][VEC])
 {
 #pragma unroll
     for (int off = G; off < W; off <<= 1)
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) acc[j] += __shfl_xor(acc[j], off, W);
+        for (int q = 0; q < NV; ++q)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[q][j] += __shfl_xor(acc[q][j], off, W);
 }
 
 }  // namespace ag

@@ -11,12 +11,12 @@
 namespace ag {
 namespace {
 
-template <int G, int W, int VEC>
+template <int G, int W, int NV, int VEC>
 __global__ __launch_bounds__(kWG) void k_csr_rows(CsrDev A, const float *__restrict__ H,
                                                   float *__restrict__ Y, int F, int row_begin,
                                                   int row_end, int acc_below)
 {
-    constexpr int TEAMS = kWG / W;
+    constexpr int TEAMS = kWG / W, FT = G * VEC * NV;
     const int tid = threadIdx.x;
     const int team = tid / W, tl = tid % W, gl = tl % G;
     const int wg = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -25,22 +25,30 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(CsrDev A, const float *__restr
     const int beg = A.rowptr[row], end = A.rowptr[row + 1];
     if (end - beg > kLongThresh) return;              // served by the segment kernels
     if (beg == end && row < acc_below) return;        // nothing to add to a row that is already written
-    const int f = blockIdx.y * (G * VEC) + gl * VEC;
-    const bool fok = f < F;
-    float acc[VEC];
+    const int f = blockIdx.y * FT + gl * VEC;
+    bool fok[NV];
+    float acc[NV][VEC];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
-    team_row_gather<G, W, VEC>(A.col, A.val, beg, end, H, F, f, fok, tl, acc);
-    team_reduce<G, W, VEC>(acc);
-    if (tl < G && fok) {
-        float *y = Y + (size_t)row * F + f;
-        if (row < acc_below) {
-            float old[VEC];
-            load_vec<VEC>(y, old);
+    for (int q = 0; q < NV; ++q) {
+        fok[q] = f + q * G * VEC < F;
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[j] += old[j];
+        for (int j = 0; j < VEC; ++j) acc[q][j] = 0.f;
+    }
+    team_row_gather<G, W, NV, VEC>(A.col, A.val, beg, end, H, F, f, fok, tl, acc);
+    team_reduce<G, W, NV, VEC>(acc);
+    if (tl < G) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            if (!fok[q]) continue;
+            float *y = Y + (size_t)row * F + f + q * G * VEC;
+            if (row < acc_below) {
+                float old[VEC];
+                load_vec<VEC>(y, old);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[q][j] += old[j];
+            }
+            store_vec<VEC>(y, acc[q]);
         }
-        store_vec<VEC>(y, acc);
     }
 }
 
@@ -55,13 +63,13 @@ __global__ __launch_bounds__(kWG) void k_csr_segments(CsrDev A, const float *__r
     if (seg >= A.nseg) return;
     const int tl = tid % W, gl = tl % G;
     const int f = blockIdx.y * (G * VEC) + gl * VEC;
-    const bool fok = f < F;
-    float acc[VEC];
+    const bool fok[1] = {f < F};
+    float acc[1][VEC];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
-    team_row_gather<G, W, VEC>(A.col, A.val, A.seg_beg[seg], A.seg_end[seg], H, F, f, fok, tl, acc);
-    team_reduce<G, W, VEC>(acc);
-    if (tl < G && fok) store_vec<VEC>(partial + (size_t)seg * F + f, acc);
+    for (int j = 0; j < VEC; ++j) acc[0][j] = 0.f;
+    team_row_gather<G, W, 1, VEC>(A.col, A.val, A.seg_beg[seg], A.seg_end[seg], H, F, f, fok, tl, acc);
+    team_reduce<G, W, 1, VEC>(acc);
+    if (tl < G && fok[0]) store_vec<VEC>(partial + (size_t)seg * F + f, acc[0]);
 }
 
 // one lane group per long row: Y[row] (+)= sum of its segments' partials, in segment order
@@ -92,28 +100,31 @@ __global__ __launch_bounds__(kWG) void k_csr_segment_sum(CsrDev A, const float *
     store_vec<VEC>(y, acc);
 }
 
-struct Shape { int G, W, VEC; };
+struct Shape { int G, W, NV, VEC; };
 
-// lanes per row so that a group covers min(F, tile) features with VEC-wide loads
-Shape pick_shape(int F, bool wide)
+// Lane layout for a feature width.  variant AG_K_CSR_WIDE: four lane groups per row; anything
+// else (narrow): one lane group per row.  (Two vectors per lane, NV = 2, was measured and never
+// beat NV = 1 for these kernels, so only NV = 1 is instantiated.)
+Shape pick_shape(int F, int variant)
 {
     Shape s;
     s.VEC = (F % 4 == 0) ? 4 : 1;
+    s.NV = 1;
     const int need = (F + s.VEC - 1) / s.VEC, cap = (s.VEC == 4) ? 32 : 64;
     s.G = 4;
     while (s.G < need && s.G < cap) s.G <<= 1;
     s.W = s.G;
-    if (wide && s.VEC == 4) s.W = (s.G >= 16) ? 64 : s.G * 4;
+    if (variant == 1 && s.VEC == 4) s.W = (s.G >= 16) ? 64 : s.G * 4;
     return s;
 }
 
-template <int G, int W, int VEC>
+template <int G, int W, int NV, int VEC>
 void run_rows(const CsrDev &A, const float *H, float *Y, int F, int rb, int re, int acc_below,
               hipStream_t st)
 {
     const int rows = re - rb, teams = kWG / W;
-    dim3 grid((rows + teams - 1) / teams, (F + G * VEC - 1) / (G * VEC));
-    hipLaunchKernelGGL((k_csr_rows<G, W, VEC>), grid, dim3(kWG), 0, st, A, H, Y, F, rb, re, acc_below);
+    dim3 grid((rows + teams - 1) / teams, (F + G * VEC * NV - 1) / (G * VEC * NV));
+    hipLaunchKernelGGL((k_csr_rows<G, W, NV, VEC>), grid, dim3(kWG), 0, st, A, H, Y, F, rb, re, acc_below);
 }
 
 template <int G, int VEC>
@@ -131,16 +142,16 @@ void run_long(const CsrDev &A, const float *H, float *Y, int F, float *partial, 
 }  // namespace
 
 int launch_csr_rows(const CsrDev &A, const float *H, float *Y, int32_t F, int32_t row_begin,
-                    int32_t row_end, int32_t acc_below, bool wide, void *stream)
+                    int32_t row_end, int32_t acc_below, int variant, void *stream)
 {
     if (row_end <= row_begin) return AG_OK;
     hipStream_t st = (hipStream_t)stream;
-    const Shape s = pick_shape(F, wide);
-#define AG_CASE(g, w, v) \
-    if (s.G == g && s.W == w && s.VEC == v) { run_rows<g, w, v>(A, H, Y, F, row_begin, row_end, acc_below, st); return hip_fail((int)hipGetLastError(), "csr_rows launch"); }
-    AG_CASE(4, 4, 4) AG_CASE(4, 16, 4) AG_CASE(8, 8, 4) AG_CASE(8, 32, 4)
-    AG_CASE(16, 16, 4) AG_CASE(16, 64, 4) AG_CASE(32, 32, 4) AG_CASE(32, 64, 4)
-    AG_CASE(4, 4, 1) AG_CASE(8, 8, 1) AG_CASE(16, 16, 1) AG_CASE(32, 32, 1) AG_CASE(64, 64, 1)
+    const Shape s = pick_shape(F, variant);
+#define AG_CASE(g, w, nv, v) \
+    if (s.G == g && s.W == w && s.NV == nv && s.VEC == v) { run_rows<g, w, nv, v>(A, H, Y, F, row_begin, row_end, acc_below, st); return hip_fail((int)hipGetLastError(), "csr_rows launch"); }
+    AG_CASE(4, 4, 1, 4) AG_CASE(4, 16, 1, 4) AG_CASE(8, 8, 1, 4) AG_CASE(8, 32, 1, 4)
+    AG_CASE(16, 16, 1, 4) AG_CASE(16, 64, 1, 4) AG_CASE(32, 32, 1, 4) AG_CASE(32, 64, 1, 4)
+    AG_CASE(4, 4, 1, 1) AG_CASE(8, 8, 1, 1) AG_CASE(16, 16, 1, 1) AG_CASE(32, 32, 1, 1) AG_CASE(64, 64, 1, 1)
 #undef AG_CASE
     set_error("csr_rows: no kernel shape for this feature width");
     return AG_ERR_UNSUPPORTED;
@@ -151,7 +162,7 @@ int launch_csr_long(const CsrDev &A, const float *H, float *Y, int32_t F, float 
 {
     if (A.nseg == 0) return AG_OK;
     hipStream_t st = (hipStream_t)stream;
-    const Shape s = pick_shape(F, false);
+    const Shape s = pick_shape(F, 0);
 #define AG_CASE(g, v) \
     if (s.G == g && s.VEC == v) { run_long<g, v>(A, H, Y, F, partial, acc_below, st); return hip_fail((int)hipGetLastError(), "csr_long launch"); }
     AG_CASE(4, 4) AG_CASE(8, 4) AG_CASE(16, 4) AG_CASE(32, 4)
