@@ -92,8 +92,12 @@ def lib() -> C.CDLL:
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
-            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2305_17408_amd.build` "
-                              "(there is no CPU fallback)")
+            # nothing built yet: compile once with hipcc; there is no CPU fallback
+            try:
+                from . import build as _build
+                _build.build()
+            except Exception as exc:
+                raise ImportError(f"{LIB_PATH} is missing and could not be built with hipcc: {exc}") from exc
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.ag_plan_create.argtypes = [C.POINTER(ag_csr), C.c_int64, C.c_int32, C.POINTER(ag_options), C.POINTER(vp)]
