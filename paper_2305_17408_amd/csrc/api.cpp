@@ -404,7 +404,7 @@ int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
     if (t.n == 0) return AG_OK;
     if (!X || !Y) { set_error("null argument"); return AG_ERR_INVALID; }
     if (X == Y) { set_error("input and output must not alias"); return AG_ERR_INVALID; }
-    if (p->F % 4 == 0 && (((uintptr_t)X | (uintptr_t)Y) & 15)) {
+    if ((((uintptr_t)X | (uintptr_t)Y) & 15)) {
         set_error("feature matrices must be 16-byte aligned");
         return AG_ERR_INVALID;
     }
@@ -572,7 +572,7 @@ int ag_permute_rows(const ag_plan *p, const float *src, float *dst, int32_t F, i
 {
     if (!p || !src || !dst || F < 1 || src == dst) { set_error("bad argument"); return AG_ERR_INVALID; }
     if (p->topo->host_only) { set_error("host-only plan"); return AG_ERR_UNSUPPORTED; }
-    if (F % 4 == 0 && (((uintptr_t)src | (uintptr_t)dst) & 15)) {
+    if ((((uintptr_t)src | (uintptr_t)dst) & 15)) {
         set_error("feature matrices must be 16-byte aligned");
         return AG_ERR_INVALID;
     }

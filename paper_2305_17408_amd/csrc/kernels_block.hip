@@ -242,6 +242,14 @@ int launch_block_sparse(const BlocksDev &B, const int32_t *list, int32_t nlist, 
         if (need > 4) return run<8, 1, 4>(B, list, nlist, fused_rem, H, Y, F, st);
         return run<4, 1, 4>(B, list, nlist, fused_rem, H, Y, F, st);
     }
+    if (F % 2 == 0) {                                   // 8-byte vectors, up to 128 features per tile
+        const int need = F / 2;
+        if (need > 32) return run<64, 1, 2>(B, list, nlist, fused_rem, H, Y, F, st);
+        if (need > 16) return run<32, 1, 2>(B, list, nlist, fused_rem, H, Y, F, st);
+        if (need > 8) return run<16, 1, 2>(B, list, nlist, fused_rem, H, Y, F, st);
+        if (need > 4) return run<8, 1, 2>(B, list, nlist, fused_rem, H, Y, F, st);
+        return run<4, 1, 2>(B, list, nlist, fused_rem, H, Y, F, st);
+    }
     if (F > 32) return run<64, 1, 1>(B, list, nlist, fused_rem, H, Y, F, st);
     if (F > 16) return run<32, 1, 1>(B, list, nlist, fused_rem, H, Y, F, st);
     if (F > 8) return run<16, 1, 1>(B, list, nlist, fused_rem, H, Y, F, st);

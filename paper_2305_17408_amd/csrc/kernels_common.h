@@ -14,6 +14,9 @@ __device__ __forceinline__ void load_vec(const float *__restrict__ p, float (&h)
     if constexpr (VEC == 4) {
         const float4 t = *reinterpret_cast<const float4 *>(p);
         h[0] = t.x; h[1] = t.y; h[2] = t.z; h[3] = t.w;
+    } else if constexpr (VEC == 2) {
+        const float2 t = *reinterpret_cast<const float2 *>(p);
+        h[0] = t.x; h[1] = t.y;
     } else {
 #pragma unroll
         for (int j = 0; j < VEC; ++j) h[j] = p[j];
@@ -25,11 +28,17 @@ __device__ __forceinline__ void store_vec(float *__restrict__ p, const float (&h
 {
     if constexpr (VEC == 4) {
         *reinterpret_cast<float4 *>(p) = make_float4(h[0], h[1], h[2], h[3]);
+    } else if constexpr (VEC == 2) {
+        *reinterpret_cast<float2 *>(p) = make_float2(h[0], h[1]);
     } else {
 #pragma unroll
         for (int j = 0; j < VEC; ++j) p[j] = h[j];
     }
 }
+
+// Widest vector (floats) every row of an F-column fp32 matrix can be moved with: rows start at
+// multiples of 4F bytes, so 16-byte vectors need F % 4 == 0 and 8-byte vectors F % 2 == 0.
+inline int vec_width(int F) { return (F % 4 == 0) ? 4 : (F % 2 == 0) ? 2 : 1; }
 
 // Work-groups are handed to the 8 XCDs round-robin.  This maps the hardware block id to a
 // logical id such that each XCD walks one contiguous eighth of the logical range, so rows

@@ -48,12 +48,13 @@ int launch_coo(const CsrDev &A, const float *H, float *Y, int32_t F, int32_t zer
     if (rc) return rc;
     const int n_edges = A.nnz;
     if (n_edges == 0) return AG_OK;
-    const int VEC = (F % 4 == 0) ? 4 : 1;
+    const int VEC = vec_width(F);
     const int need = (F + VEC - 1) / VEC, cap = (VEC == 4) ? 32 : 64;
     int G = 4;
     while (G < need && G < cap) G <<= 1;
 #define AG_CASE(g, v) if (G == g && VEC == v) { run<g, v>(A, H, Y, F, n_edges, st); return hip_fail((int)hipGetLastError(), "coo launch"); }
     AG_CASE(4, 4) AG_CASE(8, 4) AG_CASE(16, 4) AG_CASE(32, 4)
+    AG_CASE(4, 2) AG_CASE(8, 2) AG_CASE(16, 2) AG_CASE(32, 2) AG_CASE(64, 2)
     AG_CASE(4, 1) AG_CASE(8, 1) AG_CASE(16, 1) AG_CASE(32, 1) AG_CASE(64, 1)
 #undef AG_CASE
     set_error("coo: no kernel shape for this feature width");

@@ -108,7 +108,7 @@ struct Shape { int G, W, NV, VEC; };
 Shape pick_shape(int F, int variant)
 {
     Shape s;
-    s.VEC = (F % 4 == 0) ? 4 : 1;
+    s.VEC = vec_width(F);
     s.NV = 1;
     const int need = (F + s.VEC - 1) / s.VEC, cap = (s.VEC == 4) ? 32 : 64;
     s.G = 4;
@@ -151,6 +151,7 @@ int launch_csr_rows(const CsrDev &A, const float *H, float *Y, int32_t F, int32_
     if (s.G == g && s.W == w && s.NV == nv && s.VEC == v) { run_rows<g, w, nv, v>(A, H, Y, F, row_begin, row_end, acc_below, st); return hip_fail((int)hipGetLastError(), "csr_rows launch"); }
     AG_CASE(4, 4, 1, 4) AG_CASE(4, 16, 1, 4) AG_CASE(8, 8, 1, 4) AG_CASE(8, 32, 1, 4)
     AG_CASE(16, 16, 1, 4) AG_CASE(16, 64, 1, 4) AG_CASE(32, 32, 1, 4) AG_CASE(32, 64, 1, 4)
+    AG_CASE(4, 4, 1, 2) AG_CASE(8, 8, 1, 2) AG_CASE(16, 16, 1, 2) AG_CASE(32, 32, 1, 2) AG_CASE(64, 64, 1, 2)
     AG_CASE(4, 4, 1, 1) AG_CASE(8, 8, 1, 1) AG_CASE(16, 16, 1, 1) AG_CASE(32, 32, 1, 1) AG_CASE(64, 64, 1, 1)
 #undef AG_CASE
     set_error("csr_rows: no kernel shape for this feature width");
@@ -166,6 +167,7 @@ int launch_csr_long(const CsrDev &A, const float *H, float *Y, int32_t F, float 
 #define AG_CASE(g, v) \
     if (s.G == g && s.VEC == v) { run_long<g, v>(A, H, Y, F, partial, acc_below, st); return hip_fail((int)hipGetLastError(), "csr_long launch"); }
     AG_CASE(4, 4) AG_CASE(8, 4) AG_CASE(16, 4) AG_CASE(32, 4)
+    AG_CASE(4, 2) AG_CASE(8, 2) AG_CASE(16, 2) AG_CASE(32, 2) AG_CASE(64, 2)
     AG_CASE(4, 1) AG_CASE(8, 1) AG_CASE(16, 1) AG_CASE(32, 1) AG_CASE(64, 1)
 #undef AG_CASE
     set_error("csr_long: no kernel shape for this feature width");

@@ -29,6 +29,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, const float *_
     const int f0 = blockIdx.y * FT;
     const int kpad = (nr + 31) & ~31;                 // source rows rounded up, extras are zero
     if (F % 4 == 0) stage_tile<FT, 4>(H, F, r0, nr, kpad, f0, sH, tid);
+    else if (F % 2 == 0) stage_tile<FT, 2>(H, F, r0, nr, kpad, f0, sH, tid);
     else stage_tile<FT, 1>(H, F, r0, nr, kpad, f0, sH, tid);
     __syncthreads();
     const int w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;

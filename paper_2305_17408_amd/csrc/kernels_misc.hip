@@ -165,6 +165,8 @@ int launch_permute_rows(const int32_t *perm, int64_t n, int32_t F, const float *
     hipStream_t st = (hipStream_t)stream;
     if (F % 4 == 0)
         hipLaunchKernelGGL((k_permute<4>), grid1(n * (F / 4)), dim3(kWG), 0, st, perm, n, F, src, dst, inverse ? 1 : 0);
+    else if (F % 2 == 0)
+        hipLaunchKernelGGL((k_permute<2>), grid1(n * (F / 2)), dim3(kWG), 0, st, perm, n, F, src, dst, inverse ? 1 : 0);
     else
         hipLaunchKernelGGL((k_permute<1>), grid1(n * F), dim3(kWG), 0, st, perm, n, F, src, dst, inverse ? 1 : 0);
     return hip_fail((int)hipGetLastError(), "permute launch");

@@ -21,7 +21,7 @@ def test_community_size_16_as_in_the_paper():
     c.close()
 
 
-@pytest.mark.parametrize("F", [3, 36, 100, 132, 512])
+@pytest.mark.parametrize("F", [3, 36, 100, 132, 512, 66, 10])
 def test_odd_widths_with_dense_class_blocks(F):
     g = mixed_density(5, 128, 0.35, 5, 0.03, 73)
     c = Case(g, F, seed=F)

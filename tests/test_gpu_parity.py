@@ -21,7 +21,7 @@ def test_config0_all_kernel_combinations():
     c.close()
 
 
-@pytest.mark.parametrize("F", [4, 16, 32, 64, 128, 20, 7, 200, 256, 1])
+@pytest.mark.parametrize("F", [4, 16, 32, 64, 128, 20, 7, 200, 256, 1, 2, 6, 50, 66, 130, 258])
 def test_feature_widths(F):
     g = gcn_normalise(planted_partition(12, 100, 9, 0.7, 31))     # blocks of ~100: ragged tiles
     c = Case(g, F, seed=F, block_cap=100)
