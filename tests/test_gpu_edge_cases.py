@@ -155,3 +155,33 @@ def test_frozen_plan_can_be_captured_in_a_hip_graph():
         check(yo, c.Yref, c.Sy, f"graph replay {combo}")
         del graph
     c.close()
+
+
+def test_infinite_feature_reaches_only_its_neighbours():
+    """Padding / masking inside the sparse kernels must never multiply a stranger's feature row by
+    zero: an infinite feature value may only show up in rows that really reference it."""
+    import torch
+    g = gcn_normalise(planted_partition(10, 100, 8, 0.7, 97))
+    c = Case(g, 64, block_cap=100)
+    j = 123
+    H = c.H.copy()
+    H[j, :] = np.inf
+    rows = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    touched = np.zeros(g.n, bool)
+    touched[rows[g.colidx == j]] = True
+    Hfin = c.H.copy()
+    Hfin[j, :] = 0.0
+    Yfin, Sfin = oracle.spmm(g.rowptr, g.colidx, g.vals, Hfin)
+    x = torch.from_numpy(H).cuda()
+    for name in ("full_csr_narrow", "full_csr_wide", "split_sparse_narrow", "split_sparse_wide", "fused_narrow",
+                 "split_sparse_coo"):
+        force(c.plan, name, 0)
+        y = torch.empty_like(x)
+        ag.ag_aggregate(c.plan, x, y)
+        torch.cuda.synchronize()
+        yn = y.cpu().numpy().astype(np.float64)
+        assert np.all(np.isinf(yn[touched])), name                  # a_ij > 0 here: +inf
+        assert np.all(np.isfinite(yn[~touched])), name
+        err = np.abs(yn[~touched] - Yfin[~touched])
+        assert np.all(err <= 1e-5 * Sfin[~touched] + 1e-7), name
+    c.close()
