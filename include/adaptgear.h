@@ -65,7 +65,11 @@ typedef struct {
 typedef struct {
     int32_t block_cap;      /* largest community / diagonal block, 1..128 (default 128; the   *
                              * paper used 16, Sec. 2.3)                                        */
-    int32_t min_block;      /* communities smaller than this go to the block-less tail (16)    */
+    int32_t num_communities;/* alternative to block_cap (Sec. 4.2: "community size or number of  *
+                             * communities"): if > 0 and block_cap == 0, the cap becomes          *
+                             * min(128, ceil(n / num_communities))                                */
+    int32_t min_block;      /* communities smaller than this go to the block-less tail (16, or   *
+                             * the cap if that is smaller)                                        */
     int32_t sweeps;         /* label-propagation sweeps per level (8)                          */
     int32_t max_levels;     /* coarsening levels (12)                                          */
     int32_t trials;         /* timed runs per candidate in the selector (3)                    */

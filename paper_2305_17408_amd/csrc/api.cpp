@@ -452,8 +452,11 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
     if (F < 1) { set_error("F must be at least 1"); return AG_ERR_INVALID; }
     ag_options o{};
     if (opt_in) o = *opt_in;
+    if (o.num_communities < 0) { set_error("option out of range"); return AG_ERR_INVALID; }
+    if (o.block_cap == 0 && o.num_communities > 0)
+        o.block_cap = (int32_t)std::max<int64_t>(1, std::min<int64_t>(kMaxBlock, (N + o.num_communities - 1) / o.num_communities));
     if (o.block_cap == 0) o.block_cap = kMaxBlock;
-    if (o.min_block == 0) o.min_block = 16;
+    if (o.min_block == 0) o.min_block = std::min(16, o.block_cap);
     if (o.sweeps == 0) o.sweeps = 8;
     if (o.max_levels == 0) o.max_levels = 12;
     if (o.trials == 0) o.trials = 3;

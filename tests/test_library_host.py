@@ -74,6 +74,16 @@ def test_decomposition_bit_exact_directed_and_small_caps():
     compare_with_oracle(from_edges(0, np.empty(0, int), np.empty(0, int)))
 
 
+def test_number_of_communities_parameter():
+    g = gcn_normalise(planted_partition(50, 32, 6, 0.8, 9))          # n = 1600
+    p = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, 4, flags=ag.AG_FLAG_HOST_ONLY, num_communities=50)
+    e = ag.ag_plan_export(p)
+    ag.ag_plan_destroy(p)
+    r = oracle.reorder(g.rowptr, g.colidx, block_cap=32, min_block=16)   # cap = ceil(1600 / 50)
+    assert np.array_equal(e["perm"], r.perm) and np.array_equal(e["blk_ptr"], r.blk_ptr)
+    assert np.diff(e["blk_ptr"]).max() <= 32
+
+
 def test_dense_blocks_are_classified():
     g = mixed_density(8, 128, 0.3, 6, 0.02, 11)
     p = host_plan(g)
