@@ -72,6 +72,8 @@ typedef struct {
                              * the cap if that is smaller)                                        */
     int32_t sweeps;         /* label-propagation sweeps per level (8)                          */
     int32_t max_levels;     /* coarsening levels (12)                                          */
+    int32_t order_levels;   /* extra levels that only order the communities so that connected   *
+                             * ones are adjacent (3; negative = plain ascending-id order)         */
     int32_t trials;         /* timed runs per candidate in the selector (3)                    */
     int32_t layout;         /* AG_LAYOUT_*                                                     */
     int32_t flags;          /* AG_FLAG_*                                                       */

@@ -99,7 +99,7 @@ def coo_sum(n, row, col, X):
     return Y
 
 
-def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels=12):
+def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels=12, order_levels=3):
     """Community reordering (paper Sec. 2.2 / 4.2); see orc_reorder in ag_oracle.c."""
     lib = _load()
     rowptr, colidx = _i32(rowptr), _i32(colidx)
@@ -111,7 +111,8 @@ def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels
     nb = ctypes.c_int32(0)
     rc = lib.orc_reorder(ctypes.c_int64(n), _p(rowptr, ctypes.c_int32), _p(colidx, ctypes.c_int32),
                          ctypes.c_int32(block_cap), ctypes.c_int32(min_block), ctypes.c_int32(sweeps),
-                         ctypes.c_int32(max_levels), _p(perm, ctypes.c_int32), _p(iperm, ctypes.c_int32),
+                         ctypes.c_int32(max_levels), ctypes.c_int32(order_levels),
+                         _p(perm, ctypes.c_int32), _p(iperm, ctypes.c_int32),
                          _p(blk, ctypes.c_int32), ctypes.byref(nb), _p(comm, ctypes.c_int32))
     if rc:
         raise MemoryError("orc_reorder failed")

@@ -308,14 +308,24 @@ static int contract(const wgraph *g, const i32 *cluster, i32 k, wgraph *c)
  *   levels: run propagate_level, map every original vertex to its cluster,
  *   contract, and repeat on the coarse graph while a level still shrinks the
  *   node count by at least 5 % (20*k <= 19*n) and fewer than max_levels ran.
- *   layout: communities in ascending id; those with at least min_block
- *   members become diagonal blocks (members in ascending original id); all
- *   remaining vertices follow as a block-less tail in ascending original id.
+ *   layout: communities in the order described below (ascending id when no
+ *   ordering level merges anything); those with at least min_block members
+ *   become diagonal blocks (members in ascending original id); all remaining
+ *   vertices follow as a block-less tail in ascending original id.
  * Outputs: perm[new] = old, iperm[old] = new, blk_ptr[0..nb], comm[old]
  * (final community id of every original vertex).  blk_ptr needs n+1 slots.
  */
+typedef struct { i32 key[4]; i32 c; } ordkey_t;
+static int cmp_ordkey(const void *a, const void *b)
+{
+    const ordkey_t *x = (const ordkey_t *)a, *y = (const ordkey_t *)b;
+    for (int t = 0; t < 4; ++t)
+        if (x->key[t] != y->key[t]) return (x->key[t] > y->key[t]) - (x->key[t] < y->key[t]);
+    return (x->c > y->c) - (x->c < y->c);
+}
+
 int orc_reorder(i64 n, const i32 *rowptr, const i32 *col, i32 cap, i32 min_block, i32 sweeps,
-                i32 max_levels, i32 *perm, i32 *iperm, i32 *blk_ptr, i32 *nb_out, i32 *comm)
+                i32 max_levels, i32 order_levels, i32 *perm, i32 *iperm, i32 *blk_ptr, i32 *nb_out, i32 *comm)
 {
     wgraph g;
     memset(&g, 0, sizeof(g));
@@ -341,13 +351,55 @@ int orc_reorder(i64 n, const i32 *rowptr, const i32 *col, i32 cap, i32 min_block
         if (!go_on) break;
     }
     wgraph_free(&g);
+    /*
+     * Order of the communities.  Up to order_levels (<= 3) further propagation levels run on the
+     * graph of communities with the cap multiplied by 8 each time (same rules, level index > 0).
+     * They only decide the ORDER: communities are sorted by (cluster at the top level, ...,
+     * cluster at the first ordering level, community id), so communities that are strongly
+     * connected end up next to each other.  A level that merges nothing ends the sequence.
+     */
+    ordkey_t *ord = (ordkey_t *)malloc(sizeof(ordkey_t) * (size_t)(ncomm ? ncomm : 1));
+    for (i32 c = 0; c < ncomm; ++c) { ord[c].c = c; for (int t = 0; t < 4; ++t) ord[c].key[t] = 0; }
+    if (order_levels > 3) order_levels = 3;
+    if (order_levels > 0 && ncomm > 1) {
+        wgraph g0, cg;
+        memset(&g0, 0, sizeof(g0));
+        memset(&cg, 0, sizeof(cg));
+        if (build_pattern_graph(n, rowptr, col, &g0)) return -1;
+        contract(&g0, comm, ncomm, &cg);
+        wgraph_free(&g0);
+        i32 *at_node = (i32 *)malloc(sizeof(i32) * (size_t)ncomm);   /* coarse node of every community */
+        for (i32 c = 0; c < ncomm; ++c) at_node[c] = c;
+        i64 cap2 = cap;
+        for (i32 ol = 0; ol < order_levels && cg.n > 1; ++ol) {
+            cap2 *= 8;
+            if (cap2 > 0x3fffffff) cap2 = 0x3fffffff;
+            i32 *cluster = (i32 *)malloc(sizeof(i32) * (size_t)cg.n);
+            i32 kk = propagate_level(&cg, 1 + ol, (i32)cap2, sweeps, cluster);
+            if (kk == cg.n) { free(cluster); break; }
+            for (i32 c = 0; c < ncomm; ++c) {
+                at_node[c] = cluster[at_node[c]];
+                ord[c].key[2 - ol] = at_node[c];             /* higher levels are more significant */
+            }
+            wgraph nx;
+            memset(&nx, 0, sizeof(nx));
+            contract(&cg, cluster, kk, &nx);
+            wgraph_free(&cg);
+            cg = nx;
+            free(cluster);
+        }
+        wgraph_free(&cg);
+        free(at_node);
+        qsort(ord, (size_t)ncomm, sizeof(ordkey_t), cmp_ordkey);
+    }
     /* layout */
     i32 *csize = (i32 *)calloc((size_t)(ncomm ? ncomm : 1), sizeof(i32));
     for (i64 v = 0; v < n; ++v) csize[comm[v]]++;
     i32 *cstart = (i32 *)malloc(sizeof(i32) * (size_t)(ncomm ? ncomm : 1));
     i32 nb = 0, at = 0;
     blk_ptr[0] = 0;
-    for (i32 c = 0; c < ncomm; ++c) {
+    for (i32 oc = 0; oc < ncomm; ++oc) {
+        const i32 c = ord[oc].c;
         if (csize[c] >= min_block) {
             cstart[c] = at;
             at += csize[c];
@@ -362,7 +414,7 @@ int orc_reorder(i64 n, const i32 *rowptr, const i32 *col, i32 cap, i32 min_block
         iperm[v] = p;
     }
     *nb_out = nb;
-    free(csize); free(cstart);
+    free(csize); free(cstart); free(ord);
     return 0;
 }
 

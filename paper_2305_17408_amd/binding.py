@@ -39,7 +39,8 @@ class ag_csr(C.Structure):
 class ag_options(C.Structure):
     _fields_ = [("block_cap", C.c_int32), ("num_communities", C.c_int32), ("min_block", C.c_int32),
                 ("sweeps", C.c_int32),
-                ("max_levels", C.c_int32), ("trials", C.c_int32), ("layout", C.c_int32),
+                ("max_levels", C.c_int32), ("order_levels", C.c_int32), ("trials", C.c_int32),
+                ("layout", C.c_int32),
                 ("flags", C.c_int32), ("dense_density", C.c_float),
                 ("dev_alloc", C.c_void_p), ("dev_free", C.c_void_p), ("user", C.c_void_p)]
 

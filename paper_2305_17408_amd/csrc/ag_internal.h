@@ -39,7 +39,7 @@ struct ReorderResult {
 // reorder.cpp
 void build_pattern_graph(const HostCsr &A, const HostCsr &At, WGraph &g);
 void community_reorder(const WGraph &g0, int32_t cap, int32_t min_block, int32_t sweeps,
-                       int32_t max_levels, ReorderResult &out);
+                       int32_t max_levels, int32_t order_levels, ReorderResult &out);
 
 // decompose.cpp
 int  ingest_csr(const ag_csr *in, HostCsr &out, std::string &err);       // validate + sort rows

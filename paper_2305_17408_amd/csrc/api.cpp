@@ -459,6 +459,7 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
     if (o.min_block == 0) o.min_block = std::min(16, o.block_cap);
     if (o.sweeps == 0) o.sweeps = 8;
     if (o.max_levels == 0) o.max_levels = 12;
+    if (o.order_levels == 0) o.order_levels = 3;          // negative = keep the communities in id order
     if (o.trials == 0) o.trials = 3;
     if (o.dense_density == 0.f) o.dense_density = 0.20f;
     if (o.block_cap < 1 || o.block_cap > kMaxBlock || o.min_block < 1 || o.sweeps < 1 || o.max_levels < 1 ||
@@ -485,7 +486,8 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
         {
             WGraph g;
             build_pattern_graph(A0, At, g);
-            community_reorder(g, o.block_cap, o.min_block, o.sweeps, o.max_levels, t->r);
+            community_reorder(g, o.block_cap, o.min_block, o.sweeps, o.max_levels,
+                              o.order_levels < 0 ? 0 : o.order_levels, t->r);
         }
         double t1 = now_sec();
         t->sec_reorder = t1 - t0;

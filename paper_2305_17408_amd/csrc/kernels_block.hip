@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
     static_assert(kMaxBlock / TEAMS + 1 <= G, "row pointers of a team must fit in its lanes");
     extern __shared__ float sH[];                       // (kMaxBlock + 1) x FT: feature tile + a zero row
     const int tid = threadIdx.x;
-    const int b = list[blockIdx.x];
+    const int b = list[xcd_contiguous(blockIdx.x, gridDim.x)];   // neighbouring blocks share an XCD (L2)
     const int r0 = B.blk_ptr[b], nr = B.blk_ptr[b + 1] - r0;
     const int f0 = blockIdx.y * FT;
     const int team = tid / G, gl = tid % G;

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, const float *_
     constexpr int FT = 32 * NT;
     __shared__ float sH[kMaxBlock * FT];
     const int tid = threadIdx.x;
-    const int slot = blockIdx.x;
+    const int slot = xcd_contiguous(blockIdx.x, gridDim.x);   // neighbouring blocks share an XCD (L2)
     const int b = B.list_dense[slot];
     const int r0 = B.blk_ptr[b], nr = B.blk_ptr[b + 1] - r0;
     const int f0 = blockIdx.y * FT;

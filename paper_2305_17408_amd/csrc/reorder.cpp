@@ -6,6 +6,7 @@
 // communities of at least `min_block` members become the diagonal blocks of the
 // intra-community subgraph, everything else is placed behind them as a block-less tail.
 #include <algorithm>
+#include <array>
 #include <numeric>
 
 #include "ag_internal.h"
@@ -147,7 +148,7 @@ void contract(const WGraph &g, const std::vector<int32_t> &cluster, int32_t k, W
 }  // namespace
 
 void community_reorder(const WGraph &g0, int32_t cap, int32_t min_block, int32_t sweeps,
-                       int32_t max_levels, ReorderResult &out)
+                       int32_t max_levels, int32_t order_levels, ReorderResult &out)
 {
     const int32_t n = g0.n;
     out.comm.resize(n);
@@ -168,12 +169,40 @@ void community_reorder(const WGraph &g0, int32_t cap, int32_t min_block, int32_t
         coarse = std::move(next);
         g = &coarse;
     }
-    // layout: blocks (communities >= min_block, ascending id, members ascending), then the tail
+    // Order of the communities: up to three more propagation levels on the graph of communities,
+    // the cap growing 8x per level, decide only who sits next to whom (strongly connected
+    // communities become neighbours, so the remainder's gathers find their rows in a nearby L2);
+    // communities are sorted by (top-level cluster, ..., first-level cluster, id).
+    std::vector<int32_t> order(n_comm);
+    std::iota(order.begin(), order.end(), 0);
+    if (order_levels > 0 && n_comm > 1) {
+        std::vector<std::array<int32_t, 3>> key(n_comm, std::array<int32_t, 3>{0, 0, 0});
+        std::vector<int32_t> node(n_comm);
+        std::iota(node.begin(), node.end(), 0);
+        WGraph cg, nx;
+        contract(g0, out.comm, n_comm, cg);
+        int64_t cap2 = cap;
+        for (int32_t ol = 0; ol < std::min(order_levels, 3) && cg.n > 1; ++ol) {
+            cap2 = std::min<int64_t>(cap2 * 8, 0x3fffffff);
+            const int32_t kk = propagate(cg, 1 + ol, (int32_t)cap2, sweeps, cluster);
+            if (kk == cg.n) break;
+            for (int32_t c = 0; c < n_comm; ++c) {
+                node[c] = cluster[node[c]];
+                key[c][2 - ol] = node[c];
+            }
+            contract(cg, cluster, kk, nx);
+            cg = std::move(nx);
+        }
+        std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+            return key[a] != key[b] ? key[a] < key[b] : a < b;
+        });
+    }
+    // layout: blocks (communities >= min_block in that order, members ascending), then the tail
     std::vector<int32_t> csize(n_comm, 0), slot(n_comm, -1);
     for (int32_t v = 0; v < n; ++v) csize[out.comm[v]]++;
     out.blk_ptr.assign(1, 0);
     int32_t at = 0;
-    for (int32_t c = 0; c < n_comm; ++c)
+    for (int32_t c : order)
         if (csize[c] >= min_block) {
             slot[c] = at;
             at += csize[c];

@@ -33,6 +33,8 @@ def compare_with_oracle(g, **kw):
     try:
         e = ag.ag_plan_export(p)
         okw = {k: v for k, v in kw.items() if k in ("block_cap", "min_block", "sweeps", "max_levels")}
+        if "order_levels" in kw:
+            okw["order_levels"] = max(kw["order_levels"], 0)
         r = oracle.reorder(g.rowptr, g.colidx, **okw)
         assert np.array_equal(e["perm"], r.perm)
         assert np.array_equal(e["iperm"], r.iperm)
@@ -72,6 +74,8 @@ def test_decomposition_bit_exact_directed_and_small_caps():
     compare_with_oracle(planted_partition(10, 100, 10, 0.9, 5), block_cap=100, min_block=1)
     compare_with_oracle(from_edges(50, np.empty(0, int), np.empty(0, int)))
     compare_with_oracle(from_edges(0, np.empty(0, int), np.empty(0, int)))
+    compare_with_oracle(config_graph(2, scale=1 / 32), order_levels=-1)         # plain id order
+    compare_with_oracle(config_graph(2, scale=1 / 32), order_levels=1)
 
 
 def test_number_of_communities_parameter():

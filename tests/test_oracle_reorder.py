@@ -186,3 +186,35 @@ def test_golden_trace_fixture():
         assert r.comm.tolist() == list(map(int, comm.split())), name
         assert r.blk_ptr.tolist() == list(map(int, blk.split())), name
         assert r.perm.tolist() == list(map(int, perm.split())), name
+
+
+def test_ordering_levels_put_connected_communities_next_to_each_other():
+    # 12 cliques of 16; cliques (2k, 2k+1) are joined by 6 edges, nothing else.  With ids shuffled
+    # the flat order (by smallest member) interleaves the pairs; the ordering levels must make
+    # every pair adjacent.  Each clique stays its own block (cap 16).
+    rng = np.random.default_rng(3)
+    n, s = 12 * 16, 16
+    ids = rng.permutation(n)
+    us, vs = [], []
+    groups = [ids[k * s:(k + 1) * s] for k in range(12)]
+    for m in groups:
+        iu, ju = np.triu_indices(s, 1)
+        us.append(m[iu]); vs.append(m[ju])
+    for k in range(0, 12, 2):
+        us.append(groups[k][:6]); vs.append(groups[k + 1][:6])
+    g = from_edges(n, np.concatenate(us), np.concatenate(vs))
+    pair_of = np.empty(n, int)
+    for k, m in enumerate(groups):
+        pair_of[m] = k // 2
+    flat = ro(g, block_cap=16, min_block=16, order_levels=0)
+    hier = ro(g, block_cap=16, min_block=16, order_levels=3)
+    assert flat.blk_ptr.tolist() == hier.blk_ptr.tolist() == list(range(0, n + 1, 16))
+    assert sorted(hier.perm.tolist()) == list(range(n))
+    def block_pairs(r):
+        return [int(pair_of[r.perm[b * 16]]) for b in range(12)]
+    hp = block_pairs(hier)
+    assert all(hp[2 * i] == hp[2 * i + 1] for i in range(6)), hp        # partners are adjacent
+    fp = block_pairs(flat)
+    assert any(fp[2 * i] != fp[2 * i + 1] for i in range(6)), fp        # (they were not before)
+    # same communities either way
+    assert np.array_equal(np.sort(flat.comm), np.sort(hier.comm))

@@ -36,16 +36,16 @@ def random_matrix(draw):
 
 @settings(max_examples=150, deadline=None, suppress_health_check=[HealthCheck.too_slow])
 @given(g=random_matrix(), cap=st.integers(1, 128), minb=st.integers(1, 20), sweeps=st.integers(1, 8),
-       levels=st.integers(1, 12))
-def test_library_equals_oracle(g, cap, minb, sweeps, levels):
-    kw = dict(block_cap=cap, min_block=minb, sweeps=sweeps, max_levels=levels)
+       levels=st.integers(1, 12), order=st.sampled_from([-1, 1, 2, 3]))
+def test_library_equals_oracle(g, cap, minb, sweeps, levels, order):
+    kw = dict(block_cap=cap, min_block=minb, sweeps=sweeps, max_levels=levels, order_levels=order)
     p = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, 4, flags=ag.AG_FLAG_HOST_ONLY, **kw)
     try:
         e = ag.ag_plan_export(p)
         stt = ag.ag_plan_stats(p)
     finally:
         ag.ag_plan_destroy(p)
-    r = oracle.reorder(g.rowptr, g.colidx, **kw)
+    r = oracle.reorder(g.rowptr, g.colidx, **dict(kw, order_levels=max(order, 0)))
     assert np.array_equal(e["perm"], r.perm) and np.array_equal(e["iperm"], r.iperm)
     assert np.array_equal(e["blk_ptr"], r.blk_ptr)
     s = oracle.split(g.rowptr, g.colidx, g.vals, r.perm, r.iperm, r.blk_ptr)
