@@ -304,7 +304,7 @@ def main():
         log(f"[bench] cpu oracle: {multi:.2f}s with {oracle.num_threads()} threads, {single:.2f}s single-threaded")
     ag.ag_plan_destroy(plan)
     if args.all_configs:
-        out["other_workloads"] = [brief(i, max(10, args.steps // 2)) for i in range(len(CONFIGS)) if i != args.config]
+        out["other_workloads"] = [brief(i, max(50, args.steps)) for i in range(len(CONFIGS)) if i != args.config]
     print(json.dumps(out), flush=True)
 
 
