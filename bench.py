@@ -39,7 +39,7 @@ def algorithmic_bytes(st, F, compose, cls):
     wbytes = 0 if st["unit_weights"] else 4
     row = 4 * F
     if cls == 2:
-        if compose == 2:                       # one CSR over everything
+        if compose >= 2:                       # one CSR over everything
             return 4 * (n + 1) + (4 + wbytes) * st["nnz"] + row * (n + st["nnz_inter"]) + row * n
         if compose == 1:                       # tail rows only; block rows were fused
             return 0
@@ -102,7 +102,7 @@ def brief(index, steps):
             "effective_hbm_gbs": round(compulsory / ms / 1e6, 1), "selector_choice_fwd": sel["choice"],
             "trial_ms_fwd": {"dense_class": [round(x, 5) for x in t[0][:2]], "sparse_class": round(t[1][0], 5),
                              "remainder": [round(x, 5) for x in t[2][:3]],
-                             "compose_split_fused_full": [round(x, 5) for x in t[3][:3]]},
+                             "compose_split_fused_full_fullwide": [round(x, 5) for x in t[3][:4]]},
             "plan_create_s": round(t_plan, 2), "nnz_intra": st["nnz_intra"], "nnz_inter": st["nnz_inter"],
             "n_blocks": st["n_blocks"], "n_dense_blocks": st["n_dense_blocks"], "n_long_rows": st["n_long_rows"],
             "density_full": st["density_full"], "density_intra": st["density_intra"],
@@ -194,7 +194,7 @@ def main():
     if compose == 1:
         cls_names = {0: "fused block kernel (all blocks: intra from LDS + their remainder rows)",
                      1: "(unused)", 2: "tail rows + long-row segments"}
-    elif compose == 2:
+    elif compose >= 2:
         cls_names = {0: "(unused)", 1: "(unused)", 2: "one CSR over the whole reordered matrix"}
     else:
         cls_names = {0: "dense-class blocks", 1: "sparse-class blocks", 2: "remainder CSR"}
@@ -227,7 +227,7 @@ def main():
                  "achieved": round(rem_bytes / (rem_ms * 1e-3) / 1e9, 1) if rem_ms > 0 else None,
                  "frac": round(rem_bytes / (rem_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if rem_ms > 0 else None,
                  "unit": "GB/s", "peak": HBM_PEAK_GBS}
-    compose_ms = dict(zip(("split", "fused", "full_csr"), [round(t, 5) for t in sel[0]["trial_ms"][3][:3]]))
+    compose_ms = dict(zip(("split", "fused", "full_csr", "full_csr_wide"), [round(t, 5) for t in sel[0]["trial_ms"][3][:4]]))
 
     out = {
         "metric": "aggregation GFLOP/s (fwd+bwd SpMM, fp32)", "value": round(gflops, 2), "unit": "GFLOP/s",

@@ -131,7 +131,9 @@ int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int3
 /* compositions */
 #define AG_COMPOSE_SPLIT      0   /* block kernels write Y, the remainder kernel accumulates      */
 #define AG_COMPOSE_FUSED      1   /* sparse-block kernel also walks its rows' remainder           */
-#define AG_COMPOSE_FULL_CSR   2   /* no decomposition at run time: one CSR over the whole matrix  */
+#define AG_COMPOSE_FULL_CSR   2   /* no decomposition at run time: one CSR over the whole matrix, *
+                                   * one lane group per row                                       */
+#define AG_COMPOSE_FULL_CSR_WIDE 3 /* the same with several lane groups per row                   */
 
 #define AG_DIR_FWD 0
 #define AG_DIR_BWD 1

@@ -24,7 +24,7 @@ AG_CLS_BLOCKS_DENSE, AG_CLS_BLOCKS_SPARSE, AG_CLS_REMAINDER, AG_CLS_COMPOSE = 0,
 AG_NUM_CLS = 4
 AG_K_BLOCK_SPARSE, AG_K_BLOCK_DENSE = 0, 1
 AG_K_CSR_NARROW, AG_K_CSR_WIDE, AG_K_COO = 0, 1, 2
-AG_COMPOSE_SPLIT, AG_COMPOSE_FUSED, AG_COMPOSE_FULL_CSR = 0, 1, 2
+AG_COMPOSE_SPLIT, AG_COMPOSE_FUSED, AG_COMPOSE_FULL_CSR, AG_COMPOSE_FULL_CSR_WIDE = 0, 1, 2, 3
 AG_DIR_FWD, AG_DIR_BWD = 0, 1
 
 _i32p = C.POINTER(C.c_int32)

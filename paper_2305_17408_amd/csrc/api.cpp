@@ -203,7 +203,7 @@ void init_selector(ag_plan *p, int dir, bool keep_forced)
     s.ncand[AG_CLS_BLOCKS_DENSE] = t.dense_blocks.empty() ? 1 : 2;
     s.ncand[AG_CLS_BLOCKS_SPARSE] = 1;
     s.ncand[AG_CLS_REMAINDER] = 3;
-    s.ncand[AG_CLS_COMPOSE] = (t.r.n_blocks > 0) ? 3 : 1;
+    s.ncand[AG_CLS_COMPOSE] = 4;
 }
 
 int plan_device_buffers(ag_plan *p)
@@ -238,8 +238,11 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
     if (ev) (void)hipEventRecord(ev[0], st);
     switch (k[AG_CLS_COMPOSE]) {
     case AG_COMPOSE_FULL_CSR:
+    case AG_COMPOSE_FULL_CSR_WIDE:
         if (ev) { (void)hipEventRecord(ev[1], st); (void)hipEventRecord(ev[2], st); }
-        if ((rc = launch_csr_rows(D.full, H, Y, F, 0, n, 0, wide, st))) return rc;
+        if ((rc = launch_csr_rows(D.full, H, Y, F, 0, n, 0,
+                                  k[AG_CLS_COMPOSE] == AG_COMPOSE_FULL_CSR_WIDE ? AG_K_CSR_WIDE : AG_K_CSR_NARROW, st)))
+            return rc;
         if ((rc = launch_csr_long(D.full, H, Y, F, p->partial, 0, st))) return rc;
         break;
     case AG_COMPOSE_FUSED:
@@ -306,14 +309,13 @@ bool next_choice(ag_plan *p, Selector &s, int *k)
             }
             for (int c = 0; c < AG_CLS_COMPOSE; ++c)
                 k[c] = s.forced[c] >= 0 ? s.forced[c] : std::min(s.cand, s.ncand[c] - 1);
-            k[AG_CLS_COMPOSE] = (p->topo->r.n_blocks > 0) ? AG_COMPOSE_SPLIT : AG_COMPOSE_FULL_CSR;
+            k[AG_CLS_COMPOSE] = AG_COMPOSE_SPLIT;        // without blocks this is the remainder kernel alone
             return true;
         }
         if (s.phase == 1) {
             const int c = AG_CLS_COMPOSE;
-            if (s.forced[c] >= 0 || s.ncand[c] <= 1 || s.cand >= s.ncand[c]) {
+            if (s.forced[c] >= 0 || s.cand >= s.ncand[c]) {
                 finish_phase1(s);
-                if (s.ncand[c] <= 1) s.choice[c] = AG_COMPOSE_FULL_CSR;
                 s.phase = 2;
                 continue;
             }
@@ -590,7 +592,7 @@ int ag_plan_force_kernels(ag_plan *p, int32_t cls, int32_t dir, int32_t kernel_i
         set_error("bad class or direction");
         return AG_ERR_INVALID;
     }
-    static const int limit[AG_NUM_CLS] = {2, 1, 3, 3};
+    static const int limit[AG_NUM_CLS] = {2, 1, 3, 4};
     if (kernel_id < -1 || kernel_id >= 4) { set_error("kernel id out of range"); return AG_ERR_INVALID; }
     if (kernel_id >= limit[cls]) { set_error("kernel id not available for this class"); return AG_ERR_UNSUPPORTED; }
     Selector &s = p->sel[dir];
@@ -598,7 +600,6 @@ int ag_plan_force_kernels(ag_plan *p, int32_t cls, int32_t dir, int32_t kernel_i
     init_selector(p, dir, false);
     for (int c = 0; c < AG_NUM_CLS; ++c) s.forced[c] = keep[c];
     s.forced[cls] = kernel_id;
-    if (p->topo->r.n_blocks == 0) s.forced[AG_CLS_COMPOSE] = AG_COMPOSE_FULL_CSR;
     return AG_OK;
 }
 

@@ -12,7 +12,7 @@ REL, ABS = 1e-5, 1e-7
 COMBOS = {
     # name: (compose, dense-class kernel, remainder kernel)
     "full_csr_narrow": (ag.AG_COMPOSE_FULL_CSR, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_NARROW),
-    "full_csr_wide": (ag.AG_COMPOSE_FULL_CSR, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_WIDE),
+    "full_csr_wide": (ag.AG_COMPOSE_FULL_CSR_WIDE, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_WIDE),
     "split_sparse_narrow": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_NARROW),
     "split_sparse_wide": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_WIDE),
     "split_dense_narrow": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_DENSE, ag.AG_K_CSR_NARROW),

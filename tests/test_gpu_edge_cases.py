@@ -45,7 +45,7 @@ def test_no_blocks_at_all_and_tiny_graphs():
     import torch
     x = torch.from_numpy(c.H).cuda()
     y = torch.empty_like(x)
-    for _ in range(30):
+    for _ in range(48):
         ag.ag_aggregate(p, x, y)
     torch.cuda.synchronize()
     check(y, c.Yref, c.Sy, "adaptive, no blocks")
@@ -69,7 +69,7 @@ def test_non_default_stream_and_interleaved_plans():
     y1, y2 = torch.empty_like(x1), torch.empty_like(x2)
     torch.cuda.synchronize()
     with torch.cuda.stream(s):
-        for _ in range(25):                       # through the trials of both plans, interleaved
+        for _ in range(40):                       # through the trials of both plans, interleaved
             ag.ag_aggregate(c1.plan, x1, y1, stream=s)
             ag.ag_aggregate(c2.plan, x2, y2, stream=s)
     s.synchronize()

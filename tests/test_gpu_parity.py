@@ -165,7 +165,7 @@ def test_adaptive_selector_freezes_and_stays_correct():
         assert calls < 64
     info = ag.ag_plan_selector_info(c.plan, 0)
     say("selector:", info)
-    assert info["choice"][ag.AG_CLS_COMPOSE] in (0, 1, 2)
+    assert info["choice"][ag.AG_CLS_COMPOSE] in (0, 1, 2, 3)
     assert info["choice"][ag.AG_CLS_BLOCKS_DENSE] in (0, 1)
     assert info["choice"][ag.AG_CLS_REMAINDER] in (0, 1, 2)
     check(c.forward(), c.Yref, c.Sy, "after freeze")
