@@ -21,19 +21,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+AG_MIN_OWN = 256          # AG_MIN_BLOCKS_OWN_LAUNCH of the C header
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(st, F, compose, cls):
-    """Algorithmic HBM bytes of one launch of the kernel(s) of class `cls`.
+def algorithmic_bytes(st, F, compose, cls, dense_kernel=0):
+    """Algorithmic HBM bytes of one launch of the kernel(s) of class `cls` (0 dense-class blocks,
+    1 sparse-class blocks, 2 remainder / one CSR).
 
-    Remainder: its CSR arrays once, one feature-row fetch per stored entry (the sources of the
-    inter-community subgraph have no locality by construction), one write of every output
-    row, plus the read of the block rows it accumulates onto.  Blocks: block topology once,
-    every feature row once, every output row once.
+    Block kernels: the class's topology once (block CSR with one-byte columns, or for the dense
+    kernels a 2 KB bit map per block plus a 64 KB value tile if weighted), every feature row of
+    the class once, every output row once; fused, also the remainder CSR of those rows and one
+    feature-row fetch per remainder entry (the sources of the inter-community subgraph have no
+    locality by construction).  Remainder kernel (SPLIT): its CSR once, one fetch per entry, one
+    write of every output row plus the read of the block rows it accumulates onto.
     """
     n, nbr = st["n"], st["n_block_rows"]
     wbytes = 0 if st["unit_weights"] else 4
@@ -42,12 +46,27 @@ def algorithmic_bytes(st, F, compose, cls):
         if compose >= 2:                       # one CSR over everything
             return 4 * (n + 1) + (4 + wbytes) * st["nnz"] + row * (n + st["nnz_inter"]) + row * n
         if compose == 1:                       # tail rows only; block rows were fused
-            return 0
+            tail = st["nnz_inter"] - st["nnz_inter_block_rows"]
+            return 4 * (n - nbr + 1) + (4 + wbytes) * tail + row * tail + row * (n - nbr)
         return 4 * (n + 1) + (4 + wbytes) * st["nnz_inter"] + row * st["nnz_inter"] + row * n + row * nbr
-    if compose == 1 and cls == 0:              # fused block kernel: intra + remainder of block rows
-        return (4 * (nbr + 1) + (1 + wbytes) * st["nnz_intra"] + 4 * (n + 1) + (4 + wbytes) * st["nnz_inter"]
-                + row * (nbr + st["nnz_inter"]) + row * n)
-    return 4 * (nbr + 1) + (1 + wbytes) * st["nnz_intra"] + 2 * row * nbr
+    # does the dense class run its own (dense) kernel?  In the fused composition only from a minimum size on.
+    dense_own = dense_kernel != 0 and st["n_dense_blocks"] >= (AG_MIN_OWN if compose == 1 else 1)
+    d_rows, d_intra, d_inter = st["dense_rows"], st["nnz_intra_dense"], st["nnz_inter_dense_rows"]
+    if cls == 0 and dense_own:
+        rows, inter = d_rows, d_inter
+        topo = st["n_dense_blocks"] * (2048 + (0 if st["unit_weights"] else 65536))
+    else:
+        if compose == 1 and not dense_own:     # one fused kernel over all blocks
+            rows, intra, inter = nbr, st["nnz_intra"], st["nnz_inter_block_rows"]
+        elif cls == 0:
+            rows, intra, inter = d_rows, d_intra, d_inter
+        else:
+            rows, intra, inter = nbr - d_rows, st["nnz_intra"] - d_intra, st["nnz_inter_block_rows"] - d_inter
+        topo = 4 * (rows + 1) + (1 + wbytes) * intra
+    total = topo + 2 * row * rows
+    if compose == 1:
+        total += 4 * (rows + 1) + (4 + wbytes) * inter + row * inter
+    return total
 
 
 def measured_traffic(config, F, compose):
@@ -191,7 +210,12 @@ def main():
     prof = [ag.ag_plan_profile(plan, d) for d in (0, 1)]
     ag.ag_plan_set_profiling(plan, False)
     compose = prof[0]["compose"]
-    if compose == 1:
+    dense_own = sel[0]["choice"][0] != 0 and st["n_dense_blocks"] >= (AG_MIN_OWN if compose == 1 else 1)
+    if compose == 1 and dense_own:
+        cls_names = {0: "fused dense-class kernel (MFMA + the rows' remainder)",
+                     1: "fused sparse-class kernel (intra from LDS + the rows' remainder)",
+                     2: "tail rows + long-row segments"}
+    elif compose == 1:
         cls_names = {0: "fused block kernel (all blocks: intra from LDS + their remainder rows)",
                      1: "(unused)", 2: "tail rows + long-row segments"}
     elif compose >= 2:
@@ -204,13 +228,14 @@ def main():
         calls = sum(p["calls"] for p in prof)
         per_class[c] = ms / max(1, calls)
     dom = max(per_class, key=per_class.get)
-    if compose == 1 and dom == 0:
-        dom_name = "k_block_sparse<..., FUSED=true>"
-    elif dom == 2:
+    dense_names = {1: "k_block_dense", 2: "k_block_dense_bf16x3"}
+    if dom == 2:
         dom_name = "k_csr_rows (+ long-row segments)"
+    elif dom == 0 and dense_own:
+        dom_name = dense_names[sel[0]["choice"][0]] + ("<..., FUSED=true>" if compose == 1 else "")
     else:
-        dom_name = "k_block_dense" if (dom == 0 and sel[0]["choice"][0] == 1) else "k_block_sparse"
-    abytes = algorithmic_bytes(st, F, compose, dom)
+        dom_name = "k_block_sparse" + ("<..., FUSED=true>" if compose == 1 else "")
+    abytes = algorithmic_bytes(st, F, compose, dom, sel[0]["choice"][0])
     achieved = abytes / (per_class[dom] * 1e-3) / 1e9 if per_class[dom] > 0 else 0.0
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -247,7 +272,8 @@ def main():
         "remainder_path": remainder,
         "selector_trial_ms": {"compositions_fwd": compose_ms,
                               "dense_class_fwd": {"block_sparse": round(sel[0]["trial_ms"][0][0], 5),
-                                                  "dense_mfma": round(sel[0]["trial_ms"][0][1], 5)}},
+                                                  "dense_mfma_f32": round(sel[0]["trial_ms"][0][1], 5),
+                                                  "dense_mfma_bf16x3": round(sel[0]["trial_ms"][0][2], 5)}},
     }
 
     # ms per 2-layer GCN training step (only defined for the GCN workload)

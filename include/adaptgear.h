@@ -122,6 +122,9 @@ int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int3
 /* kernels for the two block classes */
 #define AG_K_BLOCK_SPARSE     0   /* block CSR with features staged in LDS (Sec. 3.2, CSR intra) */
 #define AG_K_BLOCK_DENSE      1   /* dense tile on fp32 MFMA (Sec. 3.2, dense-based kernel)       */
+#define AG_K_BLOCK_DENSE_BF16X3 2 /* the same on bf16 MFMA at fp32 accuracy: features cut into     *
+                                   * three bf16 pieces that sum to them exactly; unit-weight        *
+                                   * matrices only (AG_ERR_UNSUPPORTED otherwise)                   */
 /* kernels for the remainder: lanes cooperating on one row */
 #define AG_K_CSR_NARROW       0   /* one feature-wide lane group per row (Sec. 3.2, CSR inter)    */
 #define AG_K_CSR_WIDE         1   /* several lane groups per row, neighbours interleaved          */
@@ -130,7 +133,12 @@ int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int3
                                    * only (the other compositions fall back to AG_K_CSR_NARROW)    */
 /* compositions */
 #define AG_COMPOSE_SPLIT      0   /* block kernels write Y, the remainder kernel accumulates      */
-#define AG_COMPOSE_FUSED      1   /* sparse-block kernel also walks its rows' remainder           */
+#define AG_COMPOSE_FUSED      1   /* the block kernels also add their rows' remainder entries and *
+                                   * store each row once.  The dense class runs its own (dense)   *
+                                   * kernel here only if that kernel was chosen for it and the    *
+                                   * class has at least AG_MIN_BLOCKS_OWN_LAUNCH blocks; otherwise *
+                                   * all blocks go through the sparse-block kernel in one launch  */
+#define AG_MIN_BLOCKS_OWN_LAUNCH 256
 #define AG_COMPOSE_FULL_CSR   2   /* no decomposition at run time: one CSR over the whole matrix, *
                                    * one lane group per row                                       */
 #define AG_COMPOSE_FULL_CSR_WIDE 3 /* the same with several lane groups per row                   */
@@ -193,6 +201,9 @@ typedef struct {
     double  sec_reorder, sec_split, sec_build, sec_upload;
     int64_t device_bytes;                      /* topology held on the device                */
     int32_t block_density_hist[8];             /* diagonal blocks with density in [k/8, (k+1)/8) */
+    /* the dense class on its own (forward direction): its rows, its intra-community entries and *
+     * the remainder entries of its rows; and the remainder entries of all block rows            */
+    int64_t dense_rows, nnz_intra_dense, nnz_inter_dense_rows, nnz_inter_block_rows;
 } ag_stats;
 
 int ag_plan_stats(const ag_plan *p, ag_stats *out);

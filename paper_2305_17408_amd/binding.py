@@ -22,7 +22,8 @@ AG_LAYOUT_ORIGINAL, AG_LAYOUT_REORDERED = 0, 1
 AG_FLAG_HOST_ONLY = 1
 AG_CLS_BLOCKS_DENSE, AG_CLS_BLOCKS_SPARSE, AG_CLS_REMAINDER, AG_CLS_COMPOSE = 0, 1, 2, 3
 AG_NUM_CLS = 4
-AG_K_BLOCK_SPARSE, AG_K_BLOCK_DENSE = 0, 1
+AG_K_BLOCK_SPARSE, AG_K_BLOCK_DENSE, AG_K_BLOCK_DENSE_BF16X3 = 0, 1, 2
+AG_MIN_BLOCKS_OWN_LAUNCH = 256
 AG_K_CSR_NARROW, AG_K_CSR_WIDE, AG_K_COO = 0, 1, 2
 AG_COMPOSE_SPLIT, AG_COMPOSE_FUSED, AG_COMPOSE_FULL_CSR, AG_COMPOSE_FULL_CSR_WIDE = 0, 1, 2, 3
 AG_DIR_FWD, AG_DIR_BWD = 0, 1
@@ -66,7 +67,9 @@ class ag_stats(C.Structure):
                 ("density_full", C.c_double), ("density_intra", C.c_double), ("density_inter", C.c_double),
                 ("sec_reorder", C.c_double), ("sec_split", C.c_double), ("sec_build", C.c_double),
                 ("sec_upload", C.c_double), ("device_bytes", C.c_int64),
-                ("block_density_hist", C.c_int32 * 8)]
+                ("block_density_hist", C.c_int32 * 8),
+                ("dense_rows", C.c_int64), ("nnz_intra_dense", C.c_int64),
+                ("nnz_inter_dense_rows", C.c_int64), ("nnz_inter_block_rows", C.c_int64)]
 
 
 class ag_profile(C.Structure):

@@ -200,7 +200,7 @@ void init_selector(ag_plan *p, int dir, bool keep_forced)
     Selector &s = p->sel[dir];
     s.reset(keep_forced);
     const Topology &t = *p->topo;
-    s.ncand[AG_CLS_BLOCKS_DENSE] = t.dense_blocks.empty() ? 1 : 2;
+    s.ncand[AG_CLS_BLOCKS_DENSE] = t.dense_blocks.empty() ? 1 : (t.unit ? 3 : 2);
     s.ncand[AG_CLS_BLOCKS_SPARSE] = 1;
     s.ncand[AG_CLS_REMAINDER] = 3;
     s.ncand[AG_CLS_COMPOSE] = 4;
@@ -246,14 +246,22 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
         if ((rc = launch_csr_long(D.full, H, Y, F, p->partial, 0, st))) return rc;
         break;
     case AG_COMPOSE_FUSED:
-        if ((rc = launch_block_sparse(D.blk, D.blk.list_all, D.blk.nb, &D.inter, H, Y, F, st))) return rc;
-        if (ev) { (void)hipEventRecord(ev[1], st); (void)hipEventRecord(ev[2], st); }
+        if (k[AG_CLS_BLOCKS_DENSE] != AG_K_BLOCK_SPARSE && D.blk.n_dense >= AG_MIN_BLOCKS_OWN_LAUNCH) {
+            // the dense class keeps its own kernel, which then also adds its rows' remainder
+            if ((rc = launch_block_dense(D.blk, &D.inter, H, Y, F, k[AG_CLS_BLOCKS_DENSE], st))) return rc;
+            if (ev) (void)hipEventRecord(ev[1], st);
+            if ((rc = launch_block_sparse(D.blk, D.blk.list_sparse, D.blk.n_sparse, &D.inter, H, Y, F, st))) return rc;
+            if (ev) (void)hipEventRecord(ev[2], st);
+        } else {
+            if ((rc = launch_block_sparse(D.blk, D.blk.list_all, D.blk.nb, &D.inter, H, Y, F, st))) return rc;
+            if (ev) { (void)hipEventRecord(ev[1], st); (void)hipEventRecord(ev[2], st); }
+        }
         if ((rc = launch_csr_rows(D.inter, H, Y, F, nbr, n, 0, wide, st))) return rc;
         if ((rc = launch_csr_long(D.inter, H, Y, F, p->partial, nbr, st))) return rc;
         break;
     default:
-        if (k[AG_CLS_BLOCKS_DENSE] == AG_K_BLOCK_DENSE)
-            rc = launch_block_dense(D.blk, H, Y, F, st);
+        if (k[AG_CLS_BLOCKS_DENSE] != AG_K_BLOCK_SPARSE)
+            rc = launch_block_dense(D.blk, nullptr, H, Y, F, k[AG_CLS_BLOCKS_DENSE], st);
         else
             rc = launch_block_sparse(D.blk, D.blk.list_dense, D.blk.n_dense, nullptr, H, Y, F, st);
         if (rc) return rc;
@@ -592,9 +600,13 @@ int ag_plan_force_kernels(ag_plan *p, int32_t cls, int32_t dir, int32_t kernel_i
         set_error("bad class or direction");
         return AG_ERR_INVALID;
     }
-    static const int limit[AG_NUM_CLS] = {2, 1, 3, 4};
+    static const int limit[AG_NUM_CLS] = {3, 1, 3, 4};
     if (kernel_id < -1 || kernel_id >= 4) { set_error("kernel id out of range"); return AG_ERR_INVALID; }
     if (kernel_id >= limit[cls]) { set_error("kernel id not available for this class"); return AG_ERR_UNSUPPORTED; }
+    if (cls == AG_CLS_BLOCKS_DENSE && kernel_id == AG_K_BLOCK_DENSE_BF16X3 && !p->topo->unit) {
+        set_error("the bf16x3 dense kernel takes unit-weight matrices only");
+        return AG_ERR_UNSUPPORTED;
+    }
     Selector &s = p->sel[dir];
     const int keep[AG_NUM_CLS] = {s.forced[0], s.forced[1], s.forced[2], s.forced[3]};
     init_selector(p, dir, false);
@@ -696,6 +708,14 @@ int ag_plan_stats(const ag_plan *p, ag_stats *out)
         blk_area += s * s;
         out->block_density_hist[std::min(7, (int)(d * 8.0))]++;
     }
+    const HostCsr &O = t.h[0].inter;
+    for (int32_t b : t.dense_blocks) {
+        const int32_t r0 = t.r.blk_ptr[b], r1 = t.r.blk_ptr[b + 1];
+        out->dense_rows += r1 - r0;
+        out->nnz_intra_dense += I.rowptr[r1] - I.rowptr[r0];
+        out->nnz_inter_dense_rows += O.rowptr[r1] - O.rowptr[r0];
+    }
+    out->nnz_inter_block_rows = O.rowptr[out->n_block_rows];
     out->density_full = nn > 0 ? (double)t.nnz / nn : 0;
     out->density_intra = blk_area > 0 ? (double)out->nnz_intra / blk_area : 0;
     out->density_inter = nn - blk_area > 0 ? (double)out->nnz_inter / (nn - blk_area) : 0;

@@ -53,42 +53,6 @@ __device__ __forceinline__ void chunk_range_lds(int c, float v, int lo, int hi, 
     }
 }
 
-// the same with the feature rows gathered from global memory (U * NV loads in flight per lane)
-template <int G, int NV, int VEC>
-__device__ __forceinline__ void chunk_range_global(int c, float v, int lo, int hi, const float *__restrict__ H,
-                                                   int F, int f, const bool (&fok)[NV], float (&acc)[NV][VEC])
-{
-    constexpr int U = 4;
-    for (int k0 = lo; k0 < hi; k0 += U) {
-        int ck[U];
-        float vk[U], h[U][NV][VEC];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            ck[u] = __shfl(c, (k0 + u) & (G - 1), G);
-            vk[u] = __shfl(v, (k0 + u) & (G - 1), G);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (!(k0 + u < hi)) vk[u] = 0.f;
-#pragma unroll
-            for (int q = 0; q < NV; ++q) {
-                if (k0 + u < hi && fok[q]) {
-                    load_vec<VEC>(H + (size_t)ck[u] * F + f + q * G * VEC, h[u][q]);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) h[u][q][j] = 0.f;
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int q = 0; q < NV; ++q)
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) acc[q][j] = fmaf(vk[u], h[u][q][j], acc[q][j]);
-    }
-}
-
 template <int G, int NV, int VEC, bool FUSED>
 __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t *__restrict__ list,
                                                       CsrDev R, const float *__restrict__ H,

@@ -141,6 +141,105 @@ __device__ __forceinline__ void team_row_gather(const int32_t *__restrict__ col,
     }
 }
 
+// Entries lo..hi-1 of a register chunk (lane k of a G-lane team holds entry k: column c, value v);
+// the feature rows are gathered from global memory, U * NV loads in flight per lane.  A lane owns
+// NV vectors of VEC floats, vector q starting at column f + q*G*VEC.
+template <int G, int NV, int VEC>
+__device__ __forceinline__ void chunk_range_global(int c, float v, int lo, int hi, const float *__restrict__ H,
+                                                   int F, int f, const bool (&fok)[NV], float (&acc)[NV][VEC])
+{
+    constexpr int U = 4;
+    for (int k0 = lo; k0 < hi; k0 += U) {
+        int ck[U];
+        float vk[U], h[U][NV][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ck[u] = __shfl(c, (k0 + u) & (G - 1), G);
+            vk[u] = __shfl(v, (k0 + u) & (G - 1), G);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!(k0 + u < hi)) vk[u] = 0.f;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                if (k0 + u < hi && fok[q]) {
+                    load_vec<VEC>(H + (size_t)ck[u] * F + f + q * G * VEC, h[u][q]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) h[u][q][j] = 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[q][j] = fmaf(vk[u], h[u][q][j], acc[q][j]);
+    }
+}
+
+// Second half of a fused block kernel.  The work-group's partial sums for rows r0..r0+nr-1 and
+// columns f0..f0+FT-1 sit in the LDS tile sOut[row][FT].  A team of G = FT/VEC lanes takes a
+// contiguous run of those rows, adds the rows' entries of the remainder matrix R (feature rows
+// gathered from global memory, topology streamed through a 3-deep ring of register chunks) and
+// stores each output row exactly once.  Rows with more than kLongThresh remainder entries are
+// stored without them; the segment kernels add those afterwards.  Whole work-group must call.
+template <int FT, int VEC>
+__device__ __forceinline__ void finish_rows_with_remainder(const CsrDev &R, const float *sOut, int r0, int nr,
+                                                           const float *__restrict__ H, float *__restrict__ Y,
+                                                           int F, int f0, int tid)
+{
+    constexpr int G = FT / VEC, TEAMS = kWG / G;
+    static_assert(G <= 64 && kMaxBlock / TEAMS + 1 <= G, "row pointers of a team must fit in its lanes");
+    const int team = tid / G, gl = tid % G;
+    const int f = f0 + gl * VEC;
+    const bool fok[1] = {f < F};
+    const int rpt = (nr + TEAMS - 1) / TEAMS;
+    const int first = min(team * rpt, nr);
+    const int myrows = min(rpt, nr - first);
+    const int rrp = R.rowptr[r0 + first + min(gl, myrows)];
+    const int re1 = __shfl(rrp, myrows, G);
+    int rq = __shfl(rrp, 0, G);
+    int rc0, rc1, rc2;
+    float rv0, rv1, rv2;
+    auto ld_r = [&](int e, int &c, float &v) {
+        c = 0;
+        v = 0.f;
+        if (e < re1) {
+            c = R.col[e];
+            v = R.val ? R.val[e] : 1.f;
+        }
+    };
+    ld_r(rq + gl, rc0, rv0);
+    ld_r(rq + G + gl, rc1, rv1);
+    ld_r(rq + 2 * G + gl, rc2, rv2);
+    for (int i = 0; i < myrows; ++i) {
+        float acc[1][VEC];
+        load_vec<VEC>(sOut + (first + i) * FT + gl * VEC, acc[0]);
+        const int rb = __shfl(rrp, i, G), re = __shfl(rrp, i + 1, G);
+        int k = rb;
+        if (re - rb > kLongThresh) k = re;
+        while (k < re) {
+            if (k >= rq + 3 * G) {                      // skipped far ahead: restart the ring here
+                rq = k;
+                ld_r(rq + gl, rc0, rv0);
+                ld_r(rq + G + gl, rc1, rv1);
+                ld_r(rq + 2 * G + gl, rc2, rv2);
+            } else if (k >= rq + G) {
+                rc0 = rc1; rv0 = rv1; rc1 = rc2; rv1 = rv2;
+                rq += G;
+                ld_r(rq + 2 * G + gl, rc2, rv2);
+                continue;                               // may have to advance once more
+            }
+            const int hi = min(re, rq + G) - rq;
+            chunk_range_global<G, 1, VEC>(rc0, rv0, k - rq, hi, H, F, f, fok, acc);
+            k = rq + hi;
+        }
+        if (fok[0]) store_vec<VEC>(Y + (size_t)(r0 + first + i) * F + f, acc[0]);
+    }
+}
+
 // Sum the partial accumulators of the W/G lane groups of a team; every group ends with the total.
 template <int G, int W, int NV, int VEC>
 __device__ __forceinline__ void team_reduce(float (&acc)[NV][VEC])

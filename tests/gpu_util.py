@@ -16,11 +16,19 @@ COMBOS = {
     "split_sparse_narrow": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_NARROW),
     "split_sparse_wide": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_WIDE),
     "split_dense_narrow": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_DENSE, ag.AG_K_CSR_NARROW),
+    "split_dense_bf16x3": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_DENSE_BF16X3, ag.AG_K_CSR_NARROW),
+    "fused_dense": (ag.AG_COMPOSE_FUSED, ag.AG_K_BLOCK_DENSE, ag.AG_K_CSR_NARROW),
+    "fused_dense_bf16x3": (ag.AG_COMPOSE_FUSED, ag.AG_K_BLOCK_DENSE_BF16X3, ag.AG_K_CSR_NARROW),
     "fused_narrow": (ag.AG_COMPOSE_FUSED, ag.AG_K_BLOCK_SPARSE, ag.AG_K_CSR_NARROW),
     "split_sparse_coo": (ag.AG_COMPOSE_SPLIT, ag.AG_K_BLOCK_SPARSE, ag.AG_K_COO),
 }
 # combinations whose summation order is fixed (no atomics): bitwise reproducible run to run
 DETERMINISTIC = [k for k in COMBOS if not k.endswith("coo")]
+
+
+def usable(name, g):
+    """The bf16x3 dense kernel exists for unit-weight matrices only."""
+    return not (name.endswith("bf16x3") and g.vals is not None)
 
 
 def say(*a):
@@ -86,6 +94,8 @@ class Case:
     def check_all_combos(self, combos=None, directions=(0, 1)):
         out = {}
         for name in (combos or COMBOS):
+            if not usable(name, self.g):
+                continue
             for d in directions:
                 say(f"  combo {name} dir {d} n={self.g.n} F={self.F}")
                 force(self.plan, name, d)

@@ -9,7 +9,7 @@ import oracle
 import paper_2305_17408_amd as ag
 from ag_inputs import (config_graph, planted_partition, gcn_normalise, row_normalise, directed_random,
                        mixed_density, from_edges, features)
-from gpu_util import Case, COMBOS, DETERMINISTIC, check, force, say
+from gpu_util import Case, COMBOS, DETERMINISTIC, check, force, say, usable
 
 pytestmark = pytest.mark.gpu
 
@@ -61,7 +61,44 @@ def test_dense_class_blocks_unit_and_weighted():
         c = Case(gw, F, block_cap=96)
         assert ag.ag_plan_stats(c.plan)["n_dense_blocks"] >= 4
         c.check_all_combos(combos=["split_dense_narrow", "split_sparse_narrow"])
+        with pytest.raises(RuntimeError):            # the bf16 form has no weighted variant
+            ag.ag_plan_force_kernels(c.plan, ag.AG_CLS_BLOCKS_DENSE, 0, ag.AG_K_BLOCK_DENSE_BF16X3)
         c.close()
+    # unit weights at several widths (two 32-feature tiles, a ragged one, odd widths), ragged blocks
+    gu = mixed_density(6, 96, 0.4, 5, 0.05, 31)
+    for F in (64, 128, 24, 66, 7):
+        c = Case(gu, F, block_cap=96)
+        c.check_all_combos(combos=["split_dense_narrow", "split_dense_bf16x3"])
+        c.close()
+    # magnitudes spread over 12 decades and all 24 mantissa bits in use: the three bf16 pieces
+    # must reproduce every feature value exactly for the fp32 bound to hold
+    c = Case(gu, 32, block_cap=96)
+    rng = np.random.default_rng(77)
+    c.H = (c.H * (1.0 + 2.0 ** -23) * 10.0 ** rng.integers(-6, 7, size=c.H.shape)).astype(np.float32)
+    c.Yref, c.Sy = oracle.spmm(gu.rowptr, gu.colidx, gu.vals, c.H)
+    c.check_all_combos(combos=["split_dense_narrow", "split_dense_bf16x3"], directions=(0,))
+    c.close()
+
+
+def test_fused_dense_kernels_with_many_blocks():
+    """From AG_MIN_BLOCKS_OWN_LAUNCH dense-class blocks on, the fused composition runs the dense
+    kernels with the remainder epilogue.  One hub vertex inside a dense community gets 400 extra
+    neighbours, so its remainder row exceeds the long-row threshold and goes through the
+    segment kernels instead of the epilogue."""
+    g0 = mixed_density(272, 40, 0.45, 5, 0.05, 37)
+    rows = np.repeat(np.arange(g0.n), np.diff(g0.rowptr))
+    hub = int(np.argmax(np.diff(g0.rowptr)))
+    extra = np.random.default_rng(5).choice(g0.n, 400, replace=False)
+    gu = from_edges(g0.n, np.concatenate([rows, np.full(400, hub)]), np.concatenate([g0.colidx, extra]))
+    for g, combos, widths in ((gu, ["fused_dense", "fused_dense_bf16x3", "fused_narrow"], (32, 64, 128, 24, 66, 7)),
+                              (gcn_normalise(gu), ["fused_dense", "fused_narrow"], (32, 128, 24))):
+        for F in widths:
+            c = Case(g, F, block_cap=40)
+            st = ag.ag_plan_stats(c.plan)
+            assert st["n_dense_blocks"] >= ag.AG_MIN_BLOCKS_OWN_LAUNCH, st["n_dense_blocks"]
+            assert st["n_long_rows"] >= 1 and c.exp["iperm"][hub] < c.exp["blk_ptr"][-1]
+            c.check_all_combos(combos=combos)
+            c.close()
 
 
 def test_power_law_long_rows():
@@ -87,6 +124,8 @@ def test_exact_cases():
     g = gcn_normalise(from_edges(n, np.empty(0, int), np.empty(0, int)))
     c = Case(g, 16)
     for name in COMBOS:
+        if not usable(name, g):
+            continue
         force(c.plan, name, 0)
         y = c.forward().cpu().numpy()
         assert np.array_equal(y, c.H), name
@@ -109,6 +148,8 @@ def test_symmetric_matrix_backward_is_the_forward_kernel():
     c = Case(config_graph(0), 16)
     assert ag.ag_plan_stats(c.plan)["symmetric"] == 1
     for name in DETERMINISTIC:
+        if not usable(name, c.g):
+            continue
         force(c.plan, name, 0)
         force(c.plan, name, 1)
         c.G = c.H                                   # same input both ways
@@ -120,6 +161,8 @@ def test_runs_are_bitwise_reproducible():
     g = config_graph(2, scale=1 / 32)
     c = Case(g, 64)
     for name in DETERMINISTIC:
+        if not usable(name, c.g):
+            continue
         force(c.plan, name, 0)
         a = c.forward().cpu().numpy()
         b = c.forward().cpu().numpy()
@@ -166,7 +209,7 @@ def test_adaptive_selector_freezes_and_stays_correct():
     info = ag.ag_plan_selector_info(c.plan, 0)
     say("selector:", info)
     assert info["choice"][ag.AG_CLS_COMPOSE] in (0, 1, 2, 3)
-    assert info["choice"][ag.AG_CLS_BLOCKS_DENSE] in (0, 1)
+    assert info["choice"][ag.AG_CLS_BLOCKS_DENSE] in (0, 1, 2)
     assert info["choice"][ag.AG_CLS_REMAINDER] in (0, 1, 2)
     check(c.forward(), c.Yref, c.Sy, "after freeze")
     # backward has its own state
