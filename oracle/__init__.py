@@ -184,6 +184,46 @@ def gcn_step(rowptr, colidx, vals, X, W1, b1, W2, b2, labels):
                            db2=db2, dH1=dH1, dpre1=dpre1, dW1=dW1, db1=db1)
 
 
+def gin_step(rowptr, colidx, vals, X, Ws, bs, labels, eps=0.0):
+    """L-layer GIN forward + backward in fp64 (paper Sec. 5 "Benchmarks"; Sec. 2.1 aggregate-sum
+    followed by the Update).  Layer l: A_l = A.H_l + eps*H_l, pre_l = A_l W_l + b_l,
+    H_{l+1} = relu(pre_l) except after the last layer, whose pre-activation is the logits.
+    loss = mean softmax cross-entropy.  `vals` None = unit entries.  Returns the logits, the
+    loss and the gradient of every W_l and b_l.
+    """
+    f = np.float64
+    Ws = [np.asarray(w, f) for w in Ws]
+    bs = [np.asarray(b, f) for b in bs]
+    L = len(Ws)
+    n = np.asarray(X).shape[0]
+    H = [np.asarray(X, f)]
+    A, pre = [], []
+    for l in range(L):
+        a = _spmm64(rowptr, colidx, vals, H[l]) + eps * H[l]
+        A.append(a)
+        pre.append(a @ Ws[l] + bs[l])
+        if l < L - 1:
+            H.append(np.maximum(pre[l], 0.0))
+    Z = pre[-1]
+    zmax = Z.max(axis=1, keepdims=True)
+    ez = np.exp(Z - zmax)
+    lse = np.log(ez.sum(axis=1)) + zmax[:, 0]
+    loss = float(np.mean(lse - Z[np.arange(n), labels]))
+    dpre = ez / ez.sum(axis=1, keepdims=True)
+    dpre[np.arange(n), labels] -= 1.0
+    dpre /= n
+    dW, db = [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        dW[l] = A[l].T @ dpre
+        db[l] = dpre.sum(axis=0)
+        if l == 0:
+            break
+        dA = dpre @ Ws[l].T
+        dH = _spmm64_t(rowptr, colidx, vals, dA) + eps * dA
+        dpre = dH * (pre[l - 1] > 0.0)
+    return SimpleNamespace(Z=Z, loss=loss, dW=dW, db=db, A=A, H=H, pre=pre)
+
+
 def _spmm64(rowptr, colidx, vals, M):
     """A.M for an fp64 right-hand side (plain python/numpy row loop via CSR)."""
     rowptr, colidx = _i32(rowptr), _i32(colidx)
