@@ -119,13 +119,61 @@ def brief(index, steps):
     return {"workload": f"configs[{index}] {cfg['name']}", "n": g.n, "nnz": g.nnz, "F": F,
             "ms_per_step": round(ms, 5), "gflops": round(4.0 * g.nnz * F / ms / 1e6, 1),
             "effective_hbm_gbs": round(compulsory / ms / 1e6, 1), "selector_choice_fwd": sel["choice"],
-            "trial_ms_fwd": {"dense_class": [round(x, 5) for x in t[0][:2]], "sparse_class": round(t[1][0], 5),
+            "trial_ms_fwd": {"dense_class_bsp_f32_bf16x3": [round(x, 5) for x in t[0][:3]], "sparse_class": round(t[1][0], 5),
                              "remainder": [round(x, 5) for x in t[2][:3]],
                              "compose_split_fused_full_fullwide": [round(x, 5) for x in t[3][:4]]},
             "plan_create_s": round(t_plan, 2), "nnz_intra": st["nnz_intra"], "nnz_inter": st["nnz_inter"],
             "n_blocks": st["n_blocks"], "n_dense_blocks": st["n_dense_blocks"], "n_long_rows": st["n_long_rows"],
             "density_full": st["density_full"], "density_intra": st["density_intra"],
             "density_inter": st["density_inter"], "plan_device_bytes": st["device_bytes"]}
+
+
+def density_sweep():
+    """Kernel timings over a sweep of subgraph densities (the shape of the paper's format-versus-
+    density figure in Sec. 2.1, on synthetic graphs): (a) diagonal blocks of 128 vertices whose
+    density is swept, every block put in the dense class so that all three block kernels are timed;
+    (b) a block-less graph whose average degree is swept, timing the CSR and COO remainder kernels.
+    Times are the selector's median trial times (HIP events) of the forward direction, in ms."""
+    import torch
+    import paper_2305_17408_amd as ag
+    from ag_inputs import mixed_density, planted_partition, features
+    F = 32
+
+    def trials(g, **opts):
+        plan = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, F, layout=ag.AG_LAYOUT_REORDERED, trials=5, **opts)
+        H = torch.from_numpy(features(g.n, F, 7)).cuda()
+        Y = torch.empty_like(H)
+        n = 0
+        while n < 200 and not ag.ag_plan_selector_info(plan, 0)["frozen"]:
+            ag.ag_aggregate(plan, H, Y)
+            n += 1
+        torch.cuda.synchronize()
+        info, st = ag.ag_plan_selector_info(plan, 0), ag.ag_plan_stats(plan)
+        ag.ag_plan_destroy(plan)
+        return info, st
+
+    blocks = []
+    for p in (0.005, 0.01, 0.02, 0.05, 0.1, 0.2, 0.3, 0.5, 0.8):
+        g = mixed_density(1024, 128, p, 6, 0.02, 4000 + int(p * 1000))
+        info, st = trials(g, dense_density=1e-9)
+        t = info["trial_ms"]
+        row = {"block_density": p, "n": g.n, "nnz": g.nnz, "n_dense_class_blocks": st["n_dense_blocks"],
+               "density_intra": round(st["density_intra"], 4),
+               "block_sparse_ms": round(t[0][0], 5), "dense_f32_ms": round(t[0][1], 5),
+               "dense_bf16x3_ms": round(t[0][2], 5), "choice": info["choice"]}
+        log(f"[sweep] {row}")
+        blocks.append(row)
+    rem = []
+    for deg in (0.125, 0.25, 0.5, 1, 2, 4, 8, 16):
+        g = planted_partition(2048, 128, deg, 0.0, 5000 + int(deg * 8))
+        info, st = trials(g, min_block=129)
+        t = info["trial_ms"]
+        row = {"avg_degree": deg, "n": g.n, "nnz": g.nnz, "density": st["density_full"],
+               "csr_narrow_ms": round(t[2][0], 5), "csr_wide_ms": round(t[2][1], 5), "coo_ms": round(t[2][2], 5),
+               "choice": info["choice"]}
+        log(f"[sweep] {row}")
+        rem.append(row)
+    return {"F": F, "block_kernels_vs_block_density": blocks, "remainder_kernels_vs_degree": rem}
 
 
 def main():
@@ -138,11 +186,17 @@ def main():
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN training-step timing")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time the other four workloads (short runs) and add them under 'other_workloads'")
+    ap.add_argument("--density-sweep", action="store_true",
+                    help="instead of the benchmark, time every kernel candidate over a sweep of subgraph densities")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path is single-GPU by design); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.density_sweep:
+        print(json.dumps({"density_sweep": density_sweep()}), flush=True)
+        return
 
     import torch
     import paper_2305_17408_amd as ag
@@ -311,6 +365,47 @@ def main():
         out["gcn_loss"] = round(float(loss.item()), 6)
         log(f"[bench] GCN step {out['gcn_step_ms']} ms, loss {out['gcn_loss']}")
         ag.ag_plan_destroy(p_out)
+
+    # ms per 5-layer GIN training step (hidden 64, 16 classes) on the unit-weight GIN workload
+    if not args.no_gcn and cfg.get("norm") == "unit":
+        widths = [F, 64, 64, 64, 64, 16]
+        L = len(widths) - 1
+        by_w = {F: plan}
+        for w in widths:
+            if w not in by_w:
+                by_w[w] = ag.ag_plan_clone_for_width(plan, w)
+        plans = [by_w[w] for w in widths]
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        Wd = [t(0.05 * glorot_uniform(widths[l], widths[l + 1], 31 + l)) for l in range(L)]   # keeps activations O(1)
+        bd = [torch.zeros(widths[l + 1], device=dev) for l in range(L)]
+        dWd, dbd = [torch.empty_like(w) for w in Wd], [torch.empty_like(b) for b in bd]
+        perm = ag.ag_plan_export(plan)["perm"]
+        yl = t(labels(g.n, widths[-1], 23)[perm])
+        loss = torch.empty(1, device=dev)
+        ws = torch.empty(ag.ag_gin_workspace_bytes(g.n, widths) // 4, device=dev)
+
+        def gin():
+            ag.ag_gin_step(plans, widths=widths, eps=0.0, W=Wd, b=bd, dW=dWd, db=dbd, loss=loss, logits=None,
+                           X=Hp, labels=yl, workspace=ws)
+        n_sel = 0
+        while n_sel < 80 and not all(ag.ag_plan_selector_info(p, d)["frozen"] for p in by_w.values() for d in (0, 1)):
+            gin()
+            n_sel += 1
+        for _ in range(3):
+            gin()
+        torch.cuda.synchronize()
+        k = max(5, args.steps // 5)
+        t0 = time.perf_counter()
+        for _ in range(k):
+            gin()
+        torch.cuda.synchronize()
+        out["gin_step_ms"] = round((time.perf_counter() - t0) * 1e3 / k, 4)
+        out["gin_step_widths"] = widths
+        out["gin_loss"] = round(float(loss.item()), 6)
+        log(f"[bench] GIN step ({widths}) {out['gin_step_ms']} ms, loss {out['gin_loss']}")
+        for w, p in by_w.items():
+            if p is not plan:
+                ag.ag_plan_destroy(p)
 
     if not args.no_cpu:
         import oracle

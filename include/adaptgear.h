@@ -77,7 +77,8 @@ typedef struct {
     int32_t trials;         /* timed runs per candidate in the selector (3)                    */
     int32_t layout;         /* AG_LAYOUT_*                                                     */
     int32_t flags;          /* AG_FLAG_*                                                       */
-    float   dense_density;  /* blocks at least this dense may use the dense kernel (0.20)      */
+    float   dense_density;  /* blocks at least this dense may use the dense kernels (0.20;      *
+                             * 0.05 for unit-weight matrices, which have the bf16 form)        */
     void *(*dev_alloc)(size_t bytes, void *user);   /* default hipMalloc                       */
     void  (*dev_free)(void *ptr, void *user);       /* default hipFree                         */
     void   *user;
@@ -235,6 +236,32 @@ size_t ag_gcn_workspace_bytes(int64_t n, int32_t f_in, int32_t hidden, int32_t n
 int ag_gcn_step(ag_plan *p_in, ag_plan *p_out, const ag_gcn_io *io, const float *X_dev,
                 const int32_t *labels_dev, void *workspace_dev, size_t workspace_bytes,
                 void *hip_stream);
+
+/* L-layer GIN training step (Sec. 5 "Benchmarks": GIN; Sec. 2.1 aggregate-sum + Update), forward +
+ * backward, no optimiser update.  With H_0 = X and width[0..L] the feature widths:
+ *   A_l = A.H_l + eps*H_l                      (the stored pattern carries the unit diagonal)
+ *   H_{l+1} = relu(A_l W_l + b_l)  for l < L-1;   Z = A_{L-1} W_{L-1} + b_{L-1}
+ *   loss = mean softmax-CE(Z, labels);  gradients dW_l, db_l of every layer.
+ * The last layer is evaluated as A.(H W) when that is the narrower aggregation; backward
+ * aggregations run at the layer's output width ((A^T dPre) W^T = A^T (dPre W^T)).
+ * plans[l], l = 0..L, are AG_LAYOUT_REORDERED plans of ONE topology (ag_plan_clone_for_width) with
+ * F = width[l]; equal widths may share one plan.  All matrices are device fp32 row-major in plan
+ * order, 16-byte aligned; W[l] is width[l] x width[l+1].  Returns AG_ERR_INVALID on mismatching
+ * widths / plans / workspace size, AG_ERR_UNSUPPORTED for host-only or caller-order plans. */
+#define AG_GIN_MAX_LAYERS 8
+typedef struct {
+    int32_t n_layers;                          /* L, 1..AG_GIN_MAX_LAYERS                          */
+    int32_t width[AG_GIN_MAX_LAYERS + 1];      /* width[0] inputs ... width[L] classes             */
+    float   eps;
+    const float *W[AG_GIN_MAX_LAYERS], *b[AG_GIN_MAX_LAYERS];     /* device parameters             */
+    float *dW[AG_GIN_MAX_LAYERS], *db[AG_GIN_MAX_LAYERS];         /* device outputs, same shapes   */
+    float *loss;                               /* device, 1 float                                  */
+    float *logits;                             /* device N x width[L] output (Z), may be NULL      */
+} ag_gin_io;
+
+size_t ag_gin_workspace_bytes(int64_t n, const ag_gin_io *io);
+int ag_gin_step(ag_plan *const *plans, const ag_gin_io *io, const float *X_dev, const int32_t *labels_dev,
+                void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

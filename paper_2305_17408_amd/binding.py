@@ -77,6 +77,16 @@ class ag_profile(C.Structure):
                 ("compose", C.c_int32)]
 
 
+AG_GIN_MAX_LAYERS = 8
+
+
+class ag_gin_io(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("width", C.c_int32 * (AG_GIN_MAX_LAYERS + 1)), ("eps", C.c_float),
+                ("W", C.c_void_p * AG_GIN_MAX_LAYERS), ("b", C.c_void_p * AG_GIN_MAX_LAYERS),
+                ("dW", C.c_void_p * AG_GIN_MAX_LAYERS), ("db", C.c_void_p * AG_GIN_MAX_LAYERS),
+                ("loss", C.c_void_p), ("logits", C.c_void_p)]
+
+
 class ag_gcn_io(C.Structure):
     _fields_ = [("f_in", C.c_int32), ("hidden", C.c_int32), ("n_class", C.c_int32),
                 ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
@@ -87,7 +97,7 @@ class ag_gcn_io(C.Structure):
 EXPORTS = ["ag_plan_create", "ag_plan_clone_for_width", "ag_plan_destroy", "ag_aggregate",
            "ag_aggregate_t", "ag_permute_rows", "ag_plan_force_kernels", "ag_plan_selector_info",
            "ag_plan_export", "ag_plan_stats", "ag_plan_set_profiling", "ag_plan_profile", "ag_last_error", "ag_gin_layer", "ag_gin_layer_t",
-           "ag_gcn_workspace_bytes", "ag_gcn_step"]
+           "ag_gcn_workspace_bytes", "ag_gcn_step", "ag_gin_workspace_bytes", "ag_gin_step"]
 
 _lib = None
 
@@ -123,6 +133,9 @@ def lib() -> C.CDLL:
         L.ag_gin_layer_t.argtypes = [vp, C.c_float, vp, vp, vp]
         L.ag_gcn_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32]
         L.ag_gcn_workspace_bytes.restype = C.c_size_t
+        L.ag_gin_workspace_bytes.argtypes = [C.c_int64, C.POINTER(ag_gin_io)]
+        L.ag_gin_workspace_bytes.restype = C.c_size_t
+        L.ag_gin_step.argtypes = [C.POINTER(vp), C.POINTER(ag_gin_io), vp, vp, vp, C.c_size_t, vp]
         L.ag_gcn_step.argtypes = [vp, vp, C.POINTER(ag_gcn_io), vp, vp, vp, C.c_size_t, vp]
         _lib = L
     return _lib
@@ -261,6 +274,37 @@ def ag_gin_layer(plan, eps: float, H, Y, stream=None) -> None:
 
 def ag_gin_layer_t(plan, eps: float, G, dH, stream=None) -> None:
     _check(lib().ag_gin_layer_t(plan, float(eps), _ptr(G), _ptr(dH), _stream(stream)))
+
+
+def _gin_io(widths, eps=0.0, W=(), b=(), dW=(), db=(), loss=None, logits=None) -> ag_gin_io:
+    io = ag_gin_io()
+    io.n_layers = len(widths) - 1
+    for i, w in enumerate(widths[:AG_GIN_MAX_LAYERS + 1]):
+        io.width[i] = int(w)
+    io.eps = float(eps)
+    for name, seq in (("W", W), ("b", b), ("dW", dW), ("db", db)):
+        arr = getattr(io, name)
+        for i, t in enumerate(seq[:AG_GIN_MAX_LAYERS]):
+            arr[i] = t.data_ptr() if t is not None else None
+    io.loss = loss.data_ptr() if loss is not None else None
+    io.logits = logits.data_ptr() if logits is not None else None
+    return io
+
+
+def ag_gin_workspace_bytes(n: int, widths) -> int:
+    io = _gin_io(list(widths))
+    return int(lib().ag_gin_workspace_bytes(int(n), C.byref(io)))
+
+
+def ag_gin_step(plans, *, widths, eps, W, b, dW, db, loss, logits, X, labels, workspace, stream=None) -> None:
+    """plans[l] has F = widths[l] for l = 0..L (clones of one topology); see the C header."""
+    widths = list(widths)
+    for t in list(W) + list(b) + list(dW) + list(db) + [loss, X, labels, workspace]:
+        _ptr(t)                                           # validates device / contiguity
+    io = _gin_io(widths, eps, W, b, dW, db, loss, logits)
+    arr = (C.c_void_p * len(plans))(*plans)
+    _check(lib().ag_gin_step(arr, C.byref(io), _ptr(X), _ptr(labels), _ptr(workspace),
+                             int(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 
 def ag_gcn_workspace_bytes(n: int, f_in: int, hidden: int, n_class: int) -> int:

@@ -471,7 +471,6 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
     if (o.max_levels == 0) o.max_levels = 12;
     if (o.order_levels == 0) o.order_levels = 3;          // negative = keep the communities in id order
     if (o.trials == 0) o.trials = 3;
-    if (o.dense_density == 0.f) o.dense_density = 0.20f;
     if (o.block_cap < 1 || o.block_cap > kMaxBlock || o.min_block < 1 || o.sweeps < 1 || o.max_levels < 1 ||
         o.trials < 1 || (o.layout != AG_LAYOUT_ORIGINAL && o.layout != AG_LAYOUT_REORDERED) ||
         (!o.dev_alloc) != (!o.dev_free)) {
@@ -490,6 +489,8 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
         t->n = A0.n;
         t->nnz = A0.nnz();
         t->unit = A0.val.empty();
+        // the bf16 dense kernel (unit weights) overtakes the block-sparse kernel at far lower densities
+        if (o.dense_density == 0.f) o.dense_density = t->opt.dense_density = t->unit ? 0.05f : 0.20f;
         double t0 = now_sec();
         transpose_csr(A0, At);
         t->symmetric = bitwise_equal(A0, At);

@@ -480,9 +480,13 @@ void run_nn(int64_t N, int k, int n, const float *A, const float *W, float *C, c
                            dim3(kWG), 0, st, A, W, C, N, k, n, aux, rows_per_wg);
         return;
     }
-    if (n > 32) {
+    if (n > 64) {
         dim3 grid((unsigned)((N + 127) / 128), (n + 255) / 256);
         hipLaunchKernelGGL((k_gemm_nn<2, 2, 2, 4, EPI, 16>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
+    } else if (n > 32) {
+        // 128 x 64 tile: a wave owns 32 rows across the whole width (bandwidth-bound shape)
+        dim3 grid((unsigned)((N + 127) / 128), 1);
+        hipLaunchKernelGGL((k_gemm_nn<4, 1, 1, 2, EPI, 32>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
     } else {
         dim3 grid((unsigned)((N + 127) / 128), 1);
         hipLaunchKernelGGL((k_gemm_nn<4, 1, 1, 1, EPI, 64>), grid, dim3(kWG), 0, st, A, W, C, N, k, n, aux);
@@ -510,7 +514,11 @@ int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float 
     int nchunks = (int)std::max<int64_t>(1, std::min<int64_t>(kMaxChunks, steps));
     int64_t rows_per_chunk = ((steps + nchunks - 1) / nchunks) * kKS;
     nchunks = (int)std::max<int64_t>(1, (K + rows_per_chunk - 1) / rows_per_chunk);
-    if (n > 32) {
+    if (n > 32 && n <= 64 && m <= 64) {
+        // both widths small: a 64 x 64 tile, one 32 x 32 piece per wave
+        dim3 grid(nchunks, (m + 63) / 64, 1);
+        hipLaunchKernelGGL((k_gemm_tn<2, 2, 1, 1, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
+    } else if (n > 32) {
         dim3 grid(nchunks, (m + 127) / 128, (n + 255) / 256);
         hipLaunchKernelGGL((k_gemm_tn<2, 2, 2, 4, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     } else {

@@ -1,0 +1,112 @@
+"""GPU parity of the L-layer GIN training step against the fp64 oracle."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2305_17408_amd as ag
+from ag_inputs import (config_graph, planted_partition, mixed_density, directed_random, features, glorot_uniform,
+                       labels)
+from gpu_util import say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_step(g, widths, eps=0.0, seed=0, zero=False):
+    import torch
+    dev = "cuda"
+    L = len(widths) - 1
+    by_width = {}
+    for w in widths:                                    # one plan per distinct width, clones of the first
+        if w not in by_width:
+            by_width[w] = (ag.ag_plan_clone_for_width(by_width[widths[0]], w) if by_width else
+                           ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, w, layout=ag.AG_LAYOUT_REORDERED))
+    plans = [by_width[w] for w in widths]
+    perm = ag.ag_plan_export(plans[0])["perm"]
+    X = features(g.n, widths[0], 10 + seed)
+    Ws = [glorot_uniform(widths[l], widths[l + 1], 30 + seed + l) for l in range(L)]
+    bs = [(0.05 * features(1, widths[l + 1], 50 + seed + l)[0]).astype(np.float32) for l in range(L)]
+    if zero:
+        Ws, bs = [w * 0 for w in Ws], [b * 0 for b in bs]
+    y = labels(g.n, widths[-1], 15 + seed)
+    ref = oracle.gin_step(g.rowptr, g.colidx, g.vals, X, Ws, bs, y, eps=eps)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    Xp, yp = t(X[perm]), t(y[perm])
+    dW = [torch.full((widths[l], widths[l + 1]), float("nan"), device=dev) for l in range(L)]
+    db = [torch.full((widths[l + 1],), float("nan"), device=dev) for l in range(L)]
+    loss = torch.empty(1, device=dev)
+    logits = torch.empty(g.n, widths[-1], device=dev)
+    ws = torch.empty(ag.ag_gin_workspace_bytes(g.n, widths) // 4, device=dev)
+    Wd, bd = [t(w) for w in Ws], [t(b) for b in bs]
+    for rep in range(2):
+        ag.ag_gin_step(plans, widths=widths, eps=eps, W=Wd, b=bd, dW=dW, db=db, loss=loss, logits=logits,
+                       X=Xp, labels=yp, workspace=ws)
+    torch.cuda.synchronize()
+    for p in by_width.values():
+        ag.ag_plan_destroy(p)
+    got = dict(loss=float(loss.item()), Z=logits.cpu().numpy(), dW=[a.cpu().numpy() for a in dW],
+               db=[a.cpu().numpy() for a in db])
+    return got, ref, perm
+
+
+def compare(got, ref, perm):
+    assert abs(got["loss"] - ref.loss) <= 1e-5 * abs(ref.loss), (got["loss"], ref.loss)
+    np.testing.assert_allclose(got["Z"], ref.Z[perm], rtol=0, atol=1e-4 * np.abs(ref.Z).max())
+    for l in range(len(ref.dW)):
+        for k, a, r in (("dW", got["dW"][l], ref.dW[l]), ("db", got["db"][l], ref.db[l])):
+            err = np.abs(a - r).max()
+            assert np.isfinite(a).all() and err <= 1e-4 * np.abs(r).max(), (k, l, err, np.abs(r).max())
+
+
+@pytest.mark.parametrize("widths", [[24, 40, 8], [32, 64, 64, 64, 64, 16], [12, 20, 20], [8, 6, 10, 33], [16, 5]])
+def test_gin_step_small(widths):
+    # unit weights, mixed densities so the dense kernels take part; the wide-last-layer cases use
+    # the aggregate-first order for the last layer, the narrow ones the transform-first order
+    g = mixed_density(6, 64, 0.3, 6, 0.05, 5)
+    got, ref, perm = run_step(g, widths)
+    compare(got, ref, perm)
+
+
+def test_gin_step_directed_graph_with_eps():
+    g = directed_random(3000, 5.0, 3, weighted=False)          # a missing transpose would show
+    got, ref, perm = run_step(g, [16, 32, 32, 4], eps=0.3)
+    compare(got, ref, perm)
+
+
+def test_gin_zero_weights_loss_is_log_classes():
+    g = planted_partition(16, 64, 8, 0.7, 5)
+    got, ref, perm = run_step(g, [16, 32, 10], zero=True)
+    assert abs(got["loss"] - math.log(10.0)) < 1e-5
+
+
+def test_gin_step_rejects_mismatching_plans():
+    import torch
+    g = planted_partition(4, 64, 8, 0.7, 5)
+    p16 = ag.ag_plan_create(g.rowptr, g.colidx, None, g.n, 16, layout=ag.AG_LAYOUT_REORDERED)
+    p8 = ag.ag_plan_clone_for_width(p16, 8)
+    other = ag.ag_plan_create(g.rowptr, g.colidx, None, g.n, 8, layout=ag.AG_LAYOUT_REORDERED)
+    dev = "cuda"
+    W, b = [torch.zeros(16, 8, device=dev)], [torch.zeros(8, device=dev)]
+    dW, db = [torch.zeros(16, 8, device=dev)], [torch.zeros(8, device=dev)]
+    loss, X = torch.zeros(1, device=dev), torch.zeros(g.n, 16, device=dev)
+    y = torch.zeros(g.n, dtype=torch.int32, device=dev)
+    ws = torch.empty(ag.ag_gin_workspace_bytes(g.n, [16, 8]) // 4, device=dev)
+    kw = dict(widths=[16, 8], eps=0.0, W=W, b=b, dW=dW, db=db, loss=loss, logits=None, X=X, labels=y)
+    ag.ag_gin_step([p16, p8], workspace=ws, **kw)                          # fine
+    with pytest.raises(RuntimeError):
+        ag.ag_gin_step([p16, other], workspace=ws, **kw)                   # another topology object
+    with pytest.raises(RuntimeError):
+        ag.ag_gin_step([p8, p8], workspace=ws, **kw)                       # wrong width
+    with pytest.raises(RuntimeError):
+        ag.ag_gin_step([p16, p8], workspace=ws[: ws.numel() // 2], **kw)   # workspace too small
+    torch.cuda.synchronize()
+    for p in (p16, p8, other):
+        ag.ag_plan_destroy(p)
+
+
+def test_gin_step_config4_scaled():
+    g = config_graph(4, scale=1 / 32)
+    got, ref, perm = run_step(g, [32, 64, 64, 64, 64, 16])
+    say("loss", got["loss"], ref.loss)
+    compare(got, ref, perm)
