@@ -99,6 +99,32 @@ def coo_sum(n, row, col, X):
     return Y
 
 
+def spmax(rowptr, colidx, H):
+    """Aggregate-max (paper Sec. 2.1): Y[i][k] = max over row i's stored sources of H[j][k] and
+    the smallest source attaining it; empty rows give 0 / -1.  Edge values play no part."""
+    lib = _load()
+    rowptr, colidx, H = _i32(rowptr), _i32(colidx), _f32(H)
+    n, F = rowptr.size - 1, H.shape[1]
+    Y = np.empty((n, F), dtype=np.float64)
+    arg = np.empty((n, F), dtype=np.int32)
+    lib.orc_spmax(ctypes.c_int64(n), _p(rowptr, ctypes.c_int32), _p(colidx, ctypes.c_int32),
+                  ctypes.c_int32(F), _p(H, ctypes.c_float), _p(Y, ctypes.c_double), _p(arg, ctypes.c_int32))
+    return Y, arg
+
+
+def spmax_t(arg, G):
+    """Adjoint of spmax: dH[j][k] = sum of G[i][k] over the rows i whose maximum came from j;
+    also the same sum of |G| for the tolerance."""
+    lib = _load()
+    arg, G = _i32(arg), _f32(G)
+    n, F = G.shape
+    D = np.empty((n, F), dtype=np.float64)
+    S = np.empty((n, F), dtype=np.float64)
+    lib.orc_spmax_t(ctypes.c_int64(n), ctypes.c_int32(F), _p(arg, ctypes.c_int32), _p(G, ctypes.c_float),
+                    _p(D, ctypes.c_double), _p(S, ctypes.c_double))
+    return D, S
+
+
 def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels=12, order_levels=3):
     """Community reordering (paper Sec. 2.2 / 4.2); see orc_reorder in ag_oracle.c."""
     lib = _load()

@@ -16,6 +16,12 @@
  *   orc_spmm_t      dH = A^T.G     the adjoint, needed for training (Sec. 5
  *                                  "Benchmarks": end-to-end training).
  *   orc_coo_sum     Algorithm 1 (edge list, Y[dst] += X[src]) run serially.
+ *   orc_spmax       aggregate-max (Sec. 2.1 lists sum, mean and max as the
+ *                   Aggregate choices): Y[i][k] = max over the stored entries
+ *                   (i, j) of H[j][k], with the smallest such j as the argmax;
+ *                   rows without entries give 0 and argmax -1.
+ *   orc_spmax_t     its adjoint for training: every G[i][k] goes to the source
+ *                   vertex that attained the maximum.
  *   orc_reorder     community reordering (Sec. 2.2 / Sec. 4.2 first stage).
  *                   The paper delegates this to an external partitioner; the
  *                   reading used here is a multilevel, size-constrained label
@@ -117,6 +123,42 @@ void orc_coo_sum(i64 n, i64 E, const i32 *row, const i32 *colv, i32 F, const flo
 /* ------------------------------------------------------------------------ */
 /* Reordering                                                                */
 /* ------------------------------------------------------------------------ */
+/* ------------------------------------------------------------------------ */
+/* Y[i][k] = max_{e in row i} H[col_e][k]; arg = smallest column attaining it */
+/* ------------------------------------------------------------------------ */
+void orc_spmax(i64 n, const i32 *rowptr, const i32 *col, i32 F, const float *H, double *Y, i32 *arg)
+{
+    for (i64 i = 0; i < n; ++i) {
+        for (i32 k = 0; k < F; ++k) {
+            double best = 0.0;
+            i32 who = -1;
+            for (i32 e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                const double h = (double)H[(i64)col[e] * F + k];
+                if (who < 0 || h > best || (h == best && col[e] < who)) {
+                    best = h;
+                    who = col[e];
+                }
+            }
+            Y[i * F + k] = best;
+            arg[i * F + k] = who;
+        }
+    }
+}
+
+/* dH[j][k] = sum over rows i with arg[i][k] == j of G[i][k]; S the same sum of |G| */
+void orc_spmax_t(i64 n, i32 F, const i32 *arg, const float *G, double *D, double *S)
+{
+    for (i64 q = 0; q < n * F; ++q) { D[q] = 0.0; S[q] = 0.0; }
+    for (i64 i = 0; i < n; ++i)
+        for (i32 k = 0; k < F; ++k) {
+            const i32 j = arg[i * F + k];
+            if (j < 0) continue;
+            const double g = (double)G[i * F + k];
+            D[(i64)j * F + k] += g;
+            S[(i64)j * F + k] += fabs(g);
+        }
+}
+
 static int cmp_i32(const void *a, const void *b)
 {
     i32 x = *(const i32 *)a, y = *(const i32 *)b;
