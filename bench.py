@@ -330,6 +330,23 @@ def main():
                                                   "dense_mfma_bf16x3": round(sel[0]["trial_ms"][0][2], 5)}},
     }
 
+    # the max aggregator (forward with argmax + adjoint) on the same graph and features
+    if not args.no_gcn:
+        arg = torch.empty(g.n, F, dtype=torch.int32, device=dev)
+        for _ in range(3):
+            ag.ag_aggregate_max(plan, Hp, Y, arg)
+            ag.ag_aggregate_max_t(plan, Gp, arg, dH)
+        torch.cuda.synchronize()
+        k = max(5, args.steps // 5)
+        t0 = time.perf_counter()
+        for _ in range(k):
+            ag.ag_aggregate_max(plan, Hp, Y, arg)
+            ag.ag_aggregate_max_t(plan, Gp, arg, dH)
+        torch.cuda.synchronize()
+        out["max_aggregator_ms_per_step"] = round((time.perf_counter() - t0) * 1e3 / k, 4)
+        log(f"[bench] max aggregator fwd+adjoint {out['max_aggregator_ms_per_step']} ms/step")
+        del arg
+
     # ms per 2-layer GCN training step (only defined for the GCN workload)
     if not args.no_gcn and "hidden" in cfg:
         hid, ncls = cfg["hidden"], cfg["classes"]

@@ -211,6 +211,18 @@ int ag_plan_stats(const ag_plan *p, ag_stats *out);
 
 const char *ag_last_error(void);
 
+/* Aggregate-max (Sec. 2.1: sum, mean and max are the Aggregate choices; aggregate-mean is the sum
+ * with row-normalised edge values).  Edge values are ignored.
+ *   Y[i][k]   = max over the stored entries (i, j) of H[j][k]; rows without entries give 0
+ *   arg[i][k] = the source j that attains it, in plan numbering (-1 for rows without entries;
+ *               the smallest j among equal values); device int32 N x F, may be NULL
+ *   dH[j][k]  = sum of G[i][k] over the rows i with arg[i][k] == j   (ag_aggregate_max_t)
+ * AG_LAYOUT_REORDERED plans only (AG_ERR_UNSUPPORTED otherwise); matrices device row-major
+ * N x F in plan order, 16-byte aligned; NaN inputs are not supported.  One kernel over the whole
+ * reordered matrix; the selector plays no part.  Results are bitwise reproducible. */
+int ag_aggregate_max  (ag_plan *p, const float *H_dev, float *Y_dev, int32_t *arg_dev, void *hip_stream);
+int ag_aggregate_max_t(ag_plan *p, const float *G_dev, const int32_t *arg_dev, float *dH_dev, void *hip_stream);
+
 /* ---- model-step drivers ----------------------------------------------------------------- */
 
 /* GIN sum aggregation (Sec. 2.1 aggregate-sum, Sec. 5): Y = A.H + eps*H, where the stored

@@ -97,7 +97,7 @@ class ag_gcn_io(C.Structure):
 EXPORTS = ["ag_plan_create", "ag_plan_clone_for_width", "ag_plan_destroy", "ag_aggregate",
            "ag_aggregate_t", "ag_permute_rows", "ag_plan_force_kernels", "ag_plan_selector_info",
            "ag_plan_export", "ag_plan_stats", "ag_plan_set_profiling", "ag_plan_profile", "ag_last_error", "ag_gin_layer", "ag_gin_layer_t",
-           "ag_gcn_workspace_bytes", "ag_gcn_step", "ag_gin_workspace_bytes", "ag_gin_step"]
+           "ag_gcn_workspace_bytes", "ag_gcn_step", "ag_gin_workspace_bytes", "ag_gin_step", "ag_aggregate_max", "ag_aggregate_max_t"]
 
 _lib = None
 
@@ -133,6 +133,8 @@ def lib() -> C.CDLL:
         L.ag_gin_layer_t.argtypes = [vp, C.c_float, vp, vp, vp]
         L.ag_gcn_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32]
         L.ag_gcn_workspace_bytes.restype = C.c_size_t
+        L.ag_aggregate_max.argtypes = [vp, vp, vp, vp, vp]
+        L.ag_aggregate_max_t.argtypes = [vp, vp, vp, vp, vp]
         L.ag_gin_workspace_bytes.argtypes = [C.c_int64, C.POINTER(ag_gin_io)]
         L.ag_gin_workspace_bytes.restype = C.c_size_t
         L.ag_gin_step.argtypes = [C.POINTER(vp), C.POINTER(ag_gin_io), vp, vp, vp, C.c_size_t, vp]
@@ -274,6 +276,14 @@ def ag_gin_layer(plan, eps: float, H, Y, stream=None) -> None:
 
 def ag_gin_layer_t(plan, eps: float, G, dH, stream=None) -> None:
     _check(lib().ag_gin_layer_t(plan, float(eps), _ptr(G), _ptr(dH), _stream(stream)))
+
+
+def ag_aggregate_max(plan, H, Y, arg=None, stream=None) -> None:
+    _check(lib().ag_aggregate_max(plan, _ptr(H), _ptr(Y), _ptr(arg), _stream(stream)))
+
+
+def ag_aggregate_max_t(plan, G, arg, dH, stream=None) -> None:
+    _check(lib().ag_aggregate_max_t(plan, _ptr(G), _ptr(arg), _ptr(dH), _stream(stream)))
 
 
 def _gin_io(widths, eps=0.0, W=(), b=(), dW=(), db=(), loss=None, logits=None) -> ag_gin_io:

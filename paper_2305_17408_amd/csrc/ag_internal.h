@@ -116,6 +116,9 @@ int launch_block_sparse(const BlocksDev &B, const int32_t *list, int32_t nlist, 
 // fused_rem != null: the rows' remainder entries are added in the same kernel (one store per row)
 int launch_block_dense(const BlocksDev &B, const CsrDev *fused_rem, const float *H, float *Y, int32_t F,
                        int variant, void *stream);
+// kernels_max.hip
+int launch_csr_max(const CsrDev &A, const float *H, float *Y, int32_t *arg, int32_t F, void *stream);
+int launch_csr_max_t(const CsrDev &At, const float *G, const int32_t *arg, float *dH, int32_t F, void *stream);
 // kernels_misc.hip
 int launch_permute_rows(const int32_t *perm, int64_t n, int32_t F, const float *src, float *dst,
                         bool inverse, void *stream);

@@ -728,6 +728,43 @@ int ag_plan_stats(const ag_plan *p, ag_stats *out)
     return AG_OK;
 }
 
+namespace {
+int max_checks(ag_plan *p, const void *a, const void *b, const void *c)
+{
+    if (!p) { set_error("null plan"); return AG_ERR_INVALID; }
+    const Topology &t = *p->topo;
+    if (t.host_only) { set_error("plan was created with AG_FLAG_HOST_ONLY"); return AG_ERR_UNSUPPORTED; }
+    if (p->layout != AG_LAYOUT_REORDERED) {
+        set_error("the max aggregator needs an AG_LAYOUT_REORDERED plan");
+        return AG_ERR_UNSUPPORTED;
+    }
+    if (t.n == 0) return AG_OK;
+    if (!a || !b) { set_error("null argument"); return AG_ERR_INVALID; }
+    if (a == b) { set_error("input and output must not alias"); return AG_ERR_INVALID; }
+    if ((((uintptr_t)a | (uintptr_t)b | (uintptr_t)c) & 15)) {
+        set_error("matrices must be 16-byte aligned");
+        return AG_ERR_INVALID;
+    }
+    return AG_OK;
+}
+}  // namespace
+
+int ag_aggregate_max(ag_plan *p, const float *H, float *Y, int32_t *arg, void *stream)
+{
+    int rc = max_checks(p, H, Y, arg);
+    if (rc || p->topo->n == 0) return rc;
+    return launch_csr_max(p->topo->d[0].full, H, Y, arg, p->F, stream);
+}
+
+int ag_aggregate_max_t(ag_plan *p, const float *G, const int32_t *arg, float *dH, void *stream)
+{
+    int rc = max_checks(p, G, dH, arg);
+    if (rc || p->topo->n == 0) return rc;
+    if (!arg) { set_error("null argument"); return AG_ERR_INVALID; }
+    const Topology &t = *p->topo;
+    return launch_csr_max_t(t.d[t.symmetric ? 0 : 1].full, G, arg, dH, p->F, stream);
+}
+
 int ag_gin_layer(ag_plan *p, float eps, const float *H, float *Y, void *stream)
 {
     int rc = aggregate_dir(p, AG_DIR_FWD, H, Y, stream);
