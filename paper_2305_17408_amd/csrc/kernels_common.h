@@ -184,61 +184,74 @@ __device__ __forceinline__ void chunk_range_global(int c, float v, int lo, int h
 // contiguous run of those rows, adds the rows' entries of the remainder matrix R (feature rows
 // gathered from global memory, topology streamed through a 3-deep ring of register chunks) and
 // stores each output row exactly once.  Rows with more than kLongThresh remainder entries are
-// stored without them; the segment kernels add those afterwards.  Whole work-group must call.
+// stored without them; the segment kernels add those afterwards.
+// prepare() issues the row-pointer and first topology loads and can run long before the partial
+// sums exist (it hides two dependent memory latencies behind the block's own work); finish()
+// needs the LDS tile complete.  The whole work-group must call both.
 template <int FT, int VEC>
-__device__ __forceinline__ void finish_rows_with_remainder(const CsrDev &R, const float *sOut, int r0, int nr,
-                                                           const float *__restrict__ H, float *__restrict__ Y,
-                                                           int F, int f0, int tid)
-{
-    constexpr int G = FT / VEC, TEAMS = kWG / G;
-    static_assert(G <= 64 && kMaxBlock / TEAMS + 1 <= G, "row pointers of a team must fit in its lanes");
-    const int team = tid / G, gl = tid % G;
-    const int f = f0 + gl * VEC;
-    const bool fok[1] = {f < F};
-    const int rpt = (nr + TEAMS - 1) / TEAMS;
-    const int first = min(team * rpt, nr);
-    const int myrows = min(rpt, nr - first);
-    const int rrp = R.rowptr[r0 + first + min(gl, myrows)];
-    const int re1 = __shfl(rrp, myrows, G);
-    int rq = __shfl(rrp, 0, G);
-    int rc0, rc1, rc2;
+struct RemainderRows {
+    static constexpr int G = FT / VEC, TEAMS = kWG / (G <= kWG ? G : kWG);
+    int gl, f, first, myrows, rrp, re1, rq, rc0, rc1, rc2;
     float rv0, rv1, rv2;
-    auto ld_r = [&](int e, int &c, float &v) {
+    bool fok[1];
+
+    __device__ __forceinline__ void ld(const CsrDev &R, int e, int &c, float &v) const
+    {
         c = 0;
         v = 0.f;
         if (e < re1) {
             c = R.col[e];
             v = R.val ? R.val[e] : 1.f;
         }
-    };
-    ld_r(rq + gl, rc0, rv0);
-    ld_r(rq + G + gl, rc1, rv1);
-    ld_r(rq + 2 * G + gl, rc2, rv2);
-    for (int i = 0; i < myrows; ++i) {
-        float acc[1][VEC];
-        load_vec<VEC>(sOut + (first + i) * FT + gl * VEC, acc[0]);
-        const int rb = __shfl(rrp, i, G), re = __shfl(rrp, i + 1, G);
-        int k = rb;
-        if (re - rb > kLongThresh) k = re;
-        while (k < re) {
-            if (k >= rq + 3 * G) {                      // skipped far ahead: restart the ring here
-                rq = k;
-                ld_r(rq + gl, rc0, rv0);
-                ld_r(rq + G + gl, rc1, rv1);
-                ld_r(rq + 2 * G + gl, rc2, rv2);
-            } else if (k >= rq + G) {
-                rc0 = rc1; rv0 = rv1; rc1 = rc2; rv1 = rv2;
-                rq += G;
-                ld_r(rq + 2 * G + gl, rc2, rv2);
-                continue;                               // may have to advance once more
-            }
-            const int hi = min(re, rq + G) - rq;
-            chunk_range_global<G, 1, VEC>(rc0, rv0, k - rq, hi, H, F, f, fok, acc);
-            k = rq + hi;
-        }
-        if (fok[0]) store_vec<VEC>(Y + (size_t)(r0 + first + i) * F + f, acc[0]);
     }
-}
+
+    __device__ __forceinline__ void prepare(const CsrDev &R, int r0, int nr, int F, int f0, int tid)
+    {
+        static_assert(G <= 64 && kMaxBlock / TEAMS + 1 <= G, "row pointers of a team must fit in its lanes");
+        const int team = tid / G;
+        gl = tid % G;
+        f = f0 + gl * VEC;
+        fok[0] = f < F;
+        const int rpt = (nr + TEAMS - 1) / TEAMS;
+        first = min(team * rpt, nr);
+        myrows = min(rpt, nr - first);
+        rrp = R.rowptr[r0 + first + min(gl, myrows)];
+        re1 = __shfl(rrp, myrows, G);
+        rq = __shfl(rrp, 0, G);
+        ld(R, rq + gl, rc0, rv0);
+        ld(R, rq + G + gl, rc1, rv1);
+        ld(R, rq + 2 * G + gl, rc2, rv2);
+    }
+
+    __device__ __forceinline__ void finish(const CsrDev &R, const float *sOut, int r0,
+                                           const float *__restrict__ H, float *__restrict__ Y, int F)
+    {
+        for (int i = 0; i < myrows; ++i) {
+            float acc[1][VEC];
+            load_vec<VEC>(sOut + (first + i) * FT + gl * VEC, acc[0]);
+            const int rb = __shfl(rrp, i, G), re = __shfl(rrp, i + 1, G);
+            int k = rb;
+            if (re - rb > kLongThresh) k = re;
+            while (k < re) {
+                if (k >= rq + 3 * G) {                  // skipped far ahead: restart the ring here
+                    rq = k;
+                    ld(R, rq + gl, rc0, rv0);
+                    ld(R, rq + G + gl, rc1, rv1);
+                    ld(R, rq + 2 * G + gl, rc2, rv2);
+                } else if (k >= rq + G) {
+                    rc0 = rc1; rv0 = rv1; rc1 = rc2; rv1 = rv2;
+                    rq += G;
+                    ld(R, rq + 2 * G + gl, rc2, rv2);
+                    continue;                           // may have to advance once more
+                }
+                const int hi = min(re, rq + G) - rq;
+                chunk_range_global<G, 1, VEC>(rc0, rv0, k - rq, hi, H, F, f, fok, acc);
+                k = rq + hi;
+            }
+            if (fok[0]) store_vec<VEC>(Y + (size_t)(r0 + first + i) * F + f, acc[0]);
+        }
+    }
+};
 
 // Sum the partial accumulators of the W/G lane groups of a team; every group ends with the total.
 template <int G, int W, int NV, int VEC>

@@ -22,9 +22,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // + (r & 3)][l & 31] of the wave's 32 x 32 tile.  Plain: every lane stores its values (32
 // consecutive features per row and instruction).  FUSED: the tile goes to LDS (the operand tile
 // is no longer needed) and the rows are finished with their remainder entries, one store per row.
-template <int NT, bool FUSED>
+template <int NT, int VEC, bool FUSED>
 __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_has_rows, float *sOut,
-                                          const CsrDev &R, const float *__restrict__ H, float *__restrict__ Y,
+                                          RemainderRows<32 * NT, VEC> &rem, const CsrDev &R,
+                                          const float *__restrict__ H, float *__restrict__ Y,
                                           int F, int r0, int nr, int f0, int tid)
 {
     constexpr int FT = 32 * NT;
@@ -53,16 +54,16 @@ __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_h
                 }
         }
         __syncthreads();
-        if (F % 4 == 0) finish_rows_with_remainder<FT, 4>(R, sOut, r0, nr, H, Y, F, f0, tid);
-        else if (F % 2 == 0) finish_rows_with_remainder<FT, 2>(R, sOut, r0, nr, H, Y, F, f0, tid);
-        else finish_rows_with_remainder<FT, 1>(R, sOut, r0, nr, H, Y, F, f0, tid);
+        rem.finish(R, sOut, r0, H, Y, F);
     }
 }
 
 // Operand / result layout of the 32x32x2 fp32 instruction for lane l:
 //   A operand = A[l & 31][l >> 5], B operand = B[l >> 5][l & 31],
 //   result register r holds D[8 (r / 4) + 4 (l >> 5) + (r & 3)][l & 31].
-template <int NT, bool WEIGHTED, bool FUSED>
+// All global loads that do not depend on the staged tile (bit map, remainder row pointers and
+// first topology chunks) are issued before the staging, so they overlap with it.
+template <int NT, int VEC, bool WEIGHTED, bool FUSED>
 __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, CsrDev R, const float *__restrict__ H,
                                                      float *__restrict__ Y, int F)
 {
@@ -75,14 +76,14 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, CsrDev R, cons
     const int r0 = B.blk_ptr[b], nr = B.blk_ptr[b + 1] - r0;
     const int f0 = blockIdx.y * FT;
     const int kpad = (nr + 31) & ~31;                 // source rows rounded up, extras are zero
-    if (F % 4 == 0) stage_tile<FT, 4>(H, F, r0, nr, kpad, f0, sH, tid);
-    else if (F % 2 == 0) stage_tile<FT, 2>(H, F, r0, nr, kpad, f0, sH, tid);
-    else stage_tile<FT, 1>(H, F, r0, nr, kpad, f0, sH, tid);
-    __syncthreads();
     const int w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
     const bool has_rows = 32 * w < nr;
-    if (!FUSED && !has_rows) return;
     const uint4 bits = *reinterpret_cast<const uint4 *>(B.bitmap + ((size_t)slot * kMaxBlock + 32 * w + lo) * 4);
+    RemainderRows<FT, VEC> rem;
+    if constexpr (FUSED) rem.prepare(R, r0, nr, F, f0, tid);
+    stage_tile<FT, VEC>(H, F, r0, nr, kpad, f0, sH, tid);
+    __syncthreads();
+    if (!FUSED && !has_rows) return;
     const float *tile = WEIGHTED ? B.tiles + (size_t)slot * (kMaxBlock * kMaxBlock) + w * 4096 + l : nullptr;
     floatx16 acc[NT];
 #pragma unroll
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, CsrDev R, cons
             }
         }
     }
-    write_out<NT, FUSED>(acc, has_rows, sH, R, H, Y, F, r0, nr, f0, tid);
+    write_out<NT, VEC, FUSED>(acc, has_rows, sH, rem, R, H, Y, F, r0, nr, f0, tid);
 }
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -168,26 +169,26 @@ __device__ __forceinline__ void stage_tile_bf16x3(const float *__restrict__ H, i
 // group): A = A[l & 31][8 (l >> 5) + 0..7], B = B[8 (l >> 5) + 0..7][l & 31], result as above.
 // A is the adjacency block (rows = destinations, 8 consecutive sources = one byte of the row's
 // bit map), B the transposed feature pieces.
-template <int NT, bool FUSED>
+template <int NT, int VEC, bool FUSED>
 __global__ __launch_bounds__(kWG) void k_block_dense_bf16x3(BlocksDev B, CsrDev R, const float *__restrict__ H,
                                                             float *__restrict__ Y, int F)
 {
     constexpr int FT = 32 * NT;
     __shared__ __attribute__((aligned(16))) uint32_t sT[3 * FT * kKS / 2];
+    static_assert(3 * FT * kKS / 2 >= kMaxBlock * FT, "the result tile reuses the operand tile");
     const int tid = threadIdx.x;
     const int slot = xcd_contiguous(blockIdx.x, gridDim.x);
     const int b = B.list_dense[slot];
     const int r0 = B.blk_ptr[b], nr = B.blk_ptr[b + 1] - r0;
     const int f0 = blockIdx.y * FT;
-    if (F % 4 == 0) stage_tile_bf16x3<FT, 4>(H, F, r0, nr, f0, sT, tid);
-    else if (F % 2 == 0) stage_tile_bf16x3<FT, 2>(H, F, r0, nr, f0, sT, tid);
-    else stage_tile_bf16x3<FT, 1>(H, F, r0, nr, f0, sT, tid);
-    __syncthreads();
-    static_assert(3 * FT * kKS / 2 >= kMaxBlock * FT, "the result tile reuses the operand tile");
     const int w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
     const bool has_rows = 32 * w < nr;
-    if (!FUSED && !has_rows) return;
     const uint4 bits = *reinterpret_cast<const uint4 *>(B.bitmap + ((size_t)slot * kMaxBlock + 32 * w + lo) * 4);
+    RemainderRows<FT, VEC> rem;
+    if constexpr (FUSED) rem.prepare(R, r0, nr, F, f0, tid);
+    stage_tile_bf16x3<FT, VEC>(H, F, r0, nr, f0, sT, tid);
+    __syncthreads();
+    if (!FUSED && !has_rows) return;
     floatx16 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -214,29 +215,48 @@ __global__ __launch_bounds__(kWG) void k_block_dense_bf16x3(BlocksDev B, CsrDev 
             }
         }
     }
-    write_out<NT, FUSED>(acc, has_rows, reinterpret_cast<float *>(sT), R, H, Y, F, r0, nr, f0, tid);
+    write_out<NT, VEC, FUSED>(acc, has_rows, reinterpret_cast<float *>(sT), rem, R, H, Y, F, r0, nr, f0, tid);
 }
 
-template <int NT>
-int run_bf16x3(const BlocksDev &B, const CsrDev *rem, const float *H, float *Y, int F, hipStream_t st)
+// ---- launchers -----------------------------------------------------------------------------
+template <int NT, int VEC, bool FUSED>
+int run_bf16x3(const BlocksDev &B, const CsrDev &R, const float *H, float *Y, int F, hipStream_t st)
 {
     dim3 grid(B.n_dense, (F + 32 * NT - 1) / (32 * NT));
-    if (rem)
-        hipLaunchKernelGGL((k_block_dense_bf16x3<NT, true>), grid, dim3(kWG), 0, st, B, *rem, H, Y, F);
-    else
-        hipLaunchKernelGGL((k_block_dense_bf16x3<NT, false>), grid, dim3(kWG), 0, st, B, CsrDev(), H, Y, F);
+    hipLaunchKernelGGL((k_block_dense_bf16x3<NT, VEC, FUSED>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
     return hip_fail((int)hipGetLastError(), "block_dense_bf16x3 launch");
 }
 
-template <int NT, bool FUSED>
-int run(const BlocksDev &B, const CsrDev &R, const float *H, float *Y, int F, hipStream_t st)
+template <int NT, int VEC, bool FUSED>
+int run_f32(const BlocksDev &B, const CsrDev &R, const float *H, float *Y, int F, hipStream_t st)
 {
     dim3 grid(B.n_dense, (F + 32 * NT - 1) / (32 * NT));
     if (B.tiles)
-        hipLaunchKernelGGL((k_block_dense<NT, true, FUSED>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
+        hipLaunchKernelGGL((k_block_dense<NT, VEC, true, FUSED>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
     else
-        hipLaunchKernelGGL((k_block_dense<NT, false, FUSED>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
+        hipLaunchKernelGGL((k_block_dense<NT, VEC, false, FUSED>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
     return hip_fail((int)hipGetLastError(), "block_dense launch");
+}
+
+template <int VEC, bool FUSED>
+int pick(const BlocksDev &B, const CsrDev &R, const float *H, float *Y, int F, int variant, hipStream_t st)
+{
+    if (variant == AG_K_BLOCK_DENSE_BF16X3)
+        return (F <= 32) ? run_bf16x3<1, VEC, FUSED>(B, R, H, Y, F, st) : run_bf16x3<2, VEC, FUSED>(B, R, H, Y, F, st);
+    if (F <= 32) return run_f32<1, VEC, FUSED>(B, R, H, Y, F, st);
+    if (FUSED || F <= 64) return run_f32<2, VEC, FUSED>(B, R, H, Y, F, st);
+    if constexpr (!FUSED) return run_f32<4, VEC, false>(B, R, H, Y, F, st);
+    return AG_ERR_INVALID;                              // not reached
+}
+
+template <bool FUSED>
+int pick_vec(const BlocksDev &B, const CsrDev &R, const float *H, float *Y, int F, int variant, hipStream_t st)
+{
+    switch (vec_width(F)) {
+    case 4: return pick<4, FUSED>(B, R, H, Y, F, variant, st);
+    case 2: return pick<2, FUSED>(B, R, H, Y, F, variant, st);
+    default: return pick<1, FUSED>(B, R, H, Y, F, variant, st);
+    }
 }
 
 }  // namespace
@@ -246,17 +266,12 @@ int launch_block_dense(const BlocksDev &B, const CsrDev *fused_rem, const float 
 {
     if (B.n_dense <= 0) return AG_OK;
     hipStream_t st = (hipStream_t)stream;
-    if (variant == AG_K_BLOCK_DENSE_BF16X3) {
-        if (B.tiles) {
-            set_error("the bf16x3 dense kernel takes unit-weight blocks only");
-            return AG_ERR_UNSUPPORTED;
-        }
-        return (F <= 32) ? run_bf16x3<1>(B, fused_rem, H, Y, F, st) : run_bf16x3<2>(B, fused_rem, H, Y, F, st);
+    if (variant == AG_K_BLOCK_DENSE_BF16X3 && B.tiles) {
+        set_error("the bf16x3 dense kernel takes unit-weight blocks only");
+        return AG_ERR_UNSUPPORTED;
     }
-    if (fused_rem) return (F <= 32) ? run<1, true>(B, *fused_rem, H, Y, F, st) : run<2, true>(B, *fused_rem, H, Y, F, st);
-    if (F <= 32) return run<1, false>(B, CsrDev(), H, Y, F, st);
-    if (F <= 64) return run<2, false>(B, CsrDev(), H, Y, F, st);
-    return run<4, false>(B, CsrDev(), H, Y, F, st);
+    if (fused_rem) return pick_vec<true>(B, *fused_rem, H, Y, F, variant, st);
+    return pick_vec<false>(B, CsrDev(), H, Y, F, variant, st);
 }
 
 }  // namespace ag
