@@ -18,6 +18,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kKSdef = 16;         // K rows staged per step
 constexpr int kMaxChunks = 512;    // K-splits (partials) per output tile
+constexpr int kMaxChunksSmall = 2048;   // ... for the 64 x 64 tile: short steps need more work-groups in flight
+
+inline bool tn_small_tile(int32_t m, int32_t n) { return n > 32 && n <= 64 && m <= 64; }
+inline int tn_max_chunks(int32_t m, int32_t n) { return tn_small_tile(m, n) ? kMaxChunksSmall : kMaxChunks; }
 
 // load 4 consecutive floats of row `r` starting at column c (zero beyond `cols` / `rows`)
 __device__ __forceinline__ float4 guarded_load4(const float *__restrict__ M, int64_t r, int64_t rows,
@@ -170,25 +174,43 @@ __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, co
         }
 }
 
-__global__ __launch_bounds__(kWG) void k_sum_partials(int nchunks, int64_t count,
+__global__ __launch_bounds__(kWG) void k_sum_partials(int nchunks, int per_group, int64_t count,
                                                       const float *__restrict__ part, float *__restrict__ C)
 {
     // 32 outputs per work-group, 8 slices of the partials per output, combined through LDS in a
-    // fixed order (bitwise reproducible)
+    // fixed order (bitwise reproducible).  blockIdx.y selects a group of `per_group` partials whose
+    // sum goes to C[group][count] (one group = the plain case).
     __shared__ float red[kWG];
     const int64_t i = (int64_t)blockIdx.x * 32 + (threadIdx.x & 31);
     const int slice = threadIdx.x >> 5;
+    const int q0 = blockIdx.y * per_group, q1 = min(nchunks, q0 + per_group);
     float s = 0.f;
     if (i < count)
-        for (int q = slice; q < nchunks; q += 8) s += part[(size_t)q * count + i];
+        for (int q = q0 + slice; q < q1; q += 8) s += part[(size_t)q * count + i];
     red[threadIdx.x] = s;
     __syncthreads();
     if (threadIdx.x < 32 && i < count) {
         float t = 0.f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) t += red[k * 32 + threadIdx.x];
-        C[i] = t;
+        C[(size_t)blockIdx.y * count + i] = t;
     }
+}
+
+constexpr int kSumGroup = 128;     // partials per first-stage group when there are many K-splits
+
+// C[count] = sum of nchunks partials; with many partials in two stages (scratch2: ceil(nchunks /
+// kSumGroup) * count floats) so that the first stage fills the chip
+void sum_partials(int nchunks, int64_t count, const float *part, float *C, float *scratch2, hipStream_t st)
+{
+    const unsigned gx = (unsigned)((count + 31) / 32);
+    if (nchunks <= kMaxChunks || !scratch2) {
+        hipLaunchKernelGGL(k_sum_partials, dim3(gx), dim3(kWG), 0, st, nchunks, nchunks, count, part, C);
+        return;
+    }
+    const int groups = (nchunks + kSumGroup - 1) / kSumGroup;
+    hipLaunchKernelGGL(k_sum_partials, dim3(gx, groups), dim3(kWG), 0, st, nchunks, kSumGroup, count, part, scratch2);
+    hipLaunchKernelGGL(k_sum_partials, dim3(gx), dim3(kWG), 0, st, groups, groups, count, scratch2, C);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -495,7 +517,12 @@ void run_nn(int64_t N, int k, int n, const float *A, const float *W, float *C, c
 
 }  // namespace
 
-size_t gemm_tn_scratch_floats(int32_t m, int32_t n) { return (size_t)kMaxChunks * ((size_t)m + 1) * n; }
+size_t gemm_tn_scratch_floats(int32_t m, int32_t n)
+{
+    const size_t chunks = (size_t)tn_max_chunks(m, n);
+    const size_t stage2 = chunks > (size_t)kMaxChunks ? (chunks + kSumGroup - 1) / kSumGroup : 0;
+    return (chunks + stage2) * ((size_t)m + 1) * n;
+}
 
 // C[m x n] = A^T B, A [K x m], B [K x n]; scratch holds gemm_tn_scratch_floats(m, n) floats.
 // colsum (optional, n floats) receives the column sums of B.
@@ -508,13 +535,14 @@ int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float 
         if (colsum) { int rc = launch_fill_zero(n, colsum, stream); if (rc) return rc; }
         return launch_fill_zero((int64_t)m * n, C, stream);
     }
-    float *cs_part = colsum ? scratch + (size_t)kMaxChunks * m * n : nullptr;
+    const int max_chunks = tn_max_chunks(m, n);
+    float *cs_part = colsum ? scratch + (size_t)max_chunks * m * n : nullptr;
     const int kKS = kKSdef;
     int64_t steps = (K + kKS - 1) / kKS;
-    int nchunks = (int)std::max<int64_t>(1, std::min<int64_t>(kMaxChunks, steps));
+    int nchunks = (int)std::max<int64_t>(1, std::min<int64_t>(max_chunks, steps));
     int64_t rows_per_chunk = ((steps + nchunks - 1) / nchunks) * kKS;
     nchunks = (int)std::max<int64_t>(1, (K + rows_per_chunk - 1) / rows_per_chunk);
-    if (n > 32 && n <= 64 && m <= 64) {
+    if (tn_small_tile(m, n)) {
         // both widths small: a 64 x 64 tile, one 32 x 32 piece per wave
         dim3 grid(nchunks, (m + 63) / 64, 1);
         hipLaunchKernelGGL((k_gemm_tn<2, 2, 1, 1, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
@@ -526,11 +554,9 @@ int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float 
         hipLaunchKernelGGL((k_gemm_tn<4, 1, 2, 1, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     }
     const int64_t count = (int64_t)m * n;
-    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 31) / 32)), dim3(kWG), 0, st, nchunks,
-                       count, scratch, C);
-    if (colsum)
-        hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 31) / 32)), dim3(kWG), 0, st, nchunks,
-                           (int64_t)n, cs_part, colsum);
+    float *stage2 = max_chunks > kMaxChunks ? scratch + (size_t)max_chunks * ((size_t)m + 1) * n : nullptr;
+    sum_partials(nchunks, count, scratch, C, stage2, st);
+    if (colsum) sum_partials(nchunks, (int64_t)n, cs_part, colsum, stage2 ? stage2 + (size_t)((max_chunks + kSumGroup - 1) / kSumGroup) * count : nullptr, st);
     return hip_fail((int)hipGetLastError(), "gemm_tn launch");
 }
 
@@ -568,7 +594,7 @@ int launch_hidden_backward(int64_t N, int32_t hd, int32_t c, const float *dQ, co
     hipLaunchKernelGGL((k_hidden_backward<16>), dim3(wgs), dim3(kWG), lds, st, dQ, W2T, H1, dPre, scratch, N, c, hd,
                        kHiddenRowsPerWg);
     const int64_t count = (int64_t)hd * c;
-    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 31) / 32)), dim3(kWG), 0, st, wgs, count,
+    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 31) / 32)), dim3(kWG), 0, st, wgs, wgs, count,
                        scratch, dW2);
     return hip_fail((int)hipGetLastError(), "hidden_backward launch");
 }
