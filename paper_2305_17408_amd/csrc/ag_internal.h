@@ -134,6 +134,12 @@ int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float 
                    float *colsum, float *scratch, void *stream);
 int launch_gemm_nn(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
                    const float *aux, void *stream);
+// kernels_gemm_b3.hip
+size_t gemm_nn_b3_scratch_floats(int32_t k, int32_t n);
+int launch_gemm_nn_b3(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
+                      const float *aux, float *wsplit, void *stream);
+int launch_gemm_nn_auto(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
+                        const float *aux, float *wsplit, void *stream);
 size_t hidden_backward_scratch_floats(int64_t N, int32_t hd, int32_t c);
 int launch_hidden_backward(int64_t N, int32_t hd, int32_t c, const float *dQ, const float *W2T, const float *H1,
                            float *dPre, float *dW2, float *scratch, void *stream);

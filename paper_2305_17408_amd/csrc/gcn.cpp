@@ -22,16 +22,23 @@ using namespace ag;
 namespace {
 
 struct Ws {
-    float *P, *H1, *Q, *Z, *dZ, *dQ, *dH1, *rowloss, *W2T, *scratch;
+    float *P, *H1, *Q, *Z, *dZ, *dQ, *dH1, *rowloss, *W2T, *wsplit, *scratch;
 };
 
 // every sub-buffer starts on a 16-byte boundary (the kernels use 16-byte loads where widths allow)
 size_t pad4(size_t floats) { return (floats + 3) & ~(size_t)3; }
 
+// scratch for the split (bf16 pieces) copy of a weight matrix, largest over the transforms of the step
+size_t wsplit_floats(int32_t fi, int32_t hd, int32_t c)
+{
+    return std::max(std::max(gemm_nn_b3_scratch_floats(fi, hd), gemm_nn_b3_scratch_floats(hd, c)),
+                    gemm_nn_b3_scratch_floats(c, hd));
+}
+
 size_t ws_floats(int64_t n, int32_t fi, int32_t hd, int32_t c)
 {
     return pad4((size_t)n * fi) + 2 * pad4((size_t)n * hd) + 4 * pad4((size_t)n * c) + pad4((size_t)n) +
-           pad4((size_t)hd * c) +
+           pad4((size_t)hd * c) + pad4(wsplit_floats(fi, hd, c)) +
            std::max(std::max(col_sum_scratch_floats(std::max(hd, c)), hidden_backward_scratch_floats(n, hd, c)),
                     std::max(gemm_tn_scratch_floats(fi, hd), gemm_tn_scratch_floats(hd, c))) + 64;
 }
@@ -81,12 +88,13 @@ int ag_gcn_step(ag_plan *p_in, ag_plan *p_out, const ag_gcn_io *io, const float 
     w.dQ = q; q += pad4((size_t)n * c);
     w.rowloss = q; q += pad4((size_t)n);
     w.W2T = q; q += pad4((size_t)hd * c);
+    w.wsplit = q; q += pad4(wsplit_floats(fi, hd, c));
     w.scratch = q;
     int rc;
     // forward
     if ((rc = ag_aggregate(p_in, X, w.P, stream))) return rc;                                  // P = A X
-    if ((rc = launch_gemm_nn(n, fi, hd, w.P, io->W1, w.H1, 1, io->b1, stream))) return rc;     // H1 = relu(P W1 + b1)
-    if ((rc = launch_gemm_nn(n, hd, c, w.H1, io->W2, w.Q, 0, nullptr, stream))) return rc;     // Q = H1 W2
+    if ((rc = launch_gemm_nn_auto(n, fi, hd, w.P, io->W1, w.H1, 1, io->b1, w.wsplit, stream))) return rc;     // H1 = relu(P W1 + b1)
+    if ((rc = launch_gemm_nn_auto(n, hd, c, w.H1, io->W2, w.Q, 0, nullptr, w.wsplit, stream))) return rc;     // Q = H1 W2
     if ((rc = ag_aggregate(p_out, w.Q, w.Z, stream))) return rc;                               // Z = A Q (+ b2 below)
     if ((rc = launch_softmax_xent(n, c, w.Z, io->b2, labels, io->logits, w.dZ, w.rowloss, stream))) return rc;
     if ((rc = launch_col_sum(n, 1, w.rowloss, io->loss, w.scratch, stream))) return rc;
@@ -98,7 +106,7 @@ int ag_gcn_step(ag_plan *p_in, ag_plan *p_out, const ag_gcn_io *io, const float 
     rc = launch_hidden_backward(n, hd, c, w.dQ, w.W2T, w.H1, w.dH1, io->dW2, w.scratch, stream);
     if (rc == AG_ERR_UNSUPPORTED) {
         if ((rc = launch_gemm_tn(n, hd, c, w.H1, w.dQ, io->dW2, nullptr, w.scratch, stream))) return rc;
-        rc = launch_gemm_nn(n, c, hd, w.dQ, w.W2T, w.dH1, 2, w.H1, stream);
+        rc = launch_gemm_nn_auto(n, c, hd, w.dQ, w.W2T, w.dH1, 2, w.H1, w.wsplit, stream);
     }
     if (rc) return rc;
     if ((rc = launch_gemm_tn(n, fi, hd, w.P, w.dH1, io->dW1, io->db1, w.scratch, stream))) return rc;  // dW1 = P^T dPre, db1

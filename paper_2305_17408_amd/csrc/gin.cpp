@@ -40,7 +40,7 @@ bool last_transforms_first(const ag_gin_io *io)
 
 struct Layout {
     size_t A[AG_GIN_MAX_LAYERS], H[AG_GIN_MAX_LAYERS + 1];   // offsets (floats); H[0] unused
-    size_t Q, Z, dZ, T, dP[2], rowloss, WT, scratch, total;
+    size_t Q, Z, dZ, T, dP[2], rowloss, WT, wsplit, scratch, total;
 };
 
 Layout carve(int64_t n, const ag_gin_io *io)
@@ -51,13 +51,14 @@ Layout carve(int64_t n, const ag_gin_io *io)
     size_t at = 0;
     auto take = [&](size_t floats) { size_t o = at; at += pad4(floats); return o; };
     int32_t wmax_out = 1, whid = 1;
-    size_t wt = 1, sc = col_sum_scratch_floats(1);
+    size_t wt = 1, sc = col_sum_scratch_floats(1), wsp = 0;
     for (int l = 0; l < L; ++l) {
         const int32_t wi = io->width[l], wo = io->width[l + 1];
         if (!(tf && l == L - 1)) y.A[l] = take((size_t)n * wi);
         if (l < L - 1) { y.H[l + 1] = take((size_t)n * wo); whid = std::max(whid, wo); }
         wmax_out = std::max(wmax_out, wo);
         wt = std::max(wt, (size_t)wi * wo);
+        wsp = std::max(wsp, std::max(gemm_nn_b3_scratch_floats(wi, wo), gemm_nn_b3_scratch_floats(wo, wi)));
         sc = std::max(sc, gemm_tn_scratch_floats(wi, wo));
         sc = std::max(sc, col_sum_scratch_floats(std::max(wi, wo)));
         sc = std::max(sc, hidden_backward_scratch_floats(n, wi, wo));
@@ -71,6 +72,7 @@ Layout carve(int64_t n, const ag_gin_io *io)
     y.dP[1] = take((size_t)n * whid);
     y.rowloss = take((size_t)n);
     y.WT = take(wt);
+    y.wsplit = take(wsp + 4);
     y.scratch = take(sc + 64);
     y.total = at;
     return y;
@@ -121,6 +123,7 @@ int ag_gin_step(ag_plan *const *plans, const ag_gin_io *io, const float *X, cons
     const bool tf = last_transforms_first(io);
     const int32_t c = io->width[L];
     const float eps = io->eps;
+    float *wsplit = ws + y.wsplit;
     int rc;
 
     // ---- forward -------------------------------------------------------------------------------
@@ -131,15 +134,15 @@ int ag_gin_step(ag_plan *const *plans, const ag_gin_io *io, const float *X, cons
         if (l < L - 1) {
             float *A = ws + y.A[l], *Hn = ws + y.H[l + 1];
             if ((rc = ag_gin_layer(plans[l], eps, Hl[l], A, stream))) return rc;                       // A_l
-            if ((rc = launch_gemm_nn(n, wi, wo, A, io->W[l], Hn, 1, io->b[l], stream))) return rc;    // relu(A W + b)
+            if ((rc = launch_gemm_nn_auto(n, wi, wo, A, io->W[l], Hn, 1, io->b[l], wsplit, stream))) return rc;    // relu(A W + b)
             Hl[l + 1] = Hn;
         } else if (tf) {
-            if ((rc = launch_gemm_nn(n, wi, c, Hl[l], io->W[l], ws + y.Q, 0, nullptr, stream))) return rc;   // Q = H W
+            if ((rc = launch_gemm_nn_auto(n, wi, c, Hl[l], io->W[l], ws + y.Q, 0, nullptr, wsplit, stream))) return rc;   // Q = H W
             if ((rc = ag_gin_layer(plans[L], eps, ws + y.Q, ws + y.Z, stream))) return rc;                   // A.Q (+ b below)
         } else {
             float *A = ws + y.A[l];
             if ((rc = ag_gin_layer(plans[l], eps, Hl[l], A, stream))) return rc;
-            if ((rc = launch_gemm_nn(n, wi, c, A, io->W[l], ws + y.Z, 0, nullptr, stream))) return rc;
+            if ((rc = launch_gemm_nn_auto(n, wi, c, A, io->W[l], ws + y.Z, 0, nullptr, wsplit, stream))) return rc;
         }
     }
     float *dZ = ws + y.dZ, *scratch = ws + y.scratch, *T = ws + y.T, *WT = ws + y.WT;
@@ -163,7 +166,7 @@ int ag_gin_step(ag_plan *const *plans, const ag_gin_io *io, const float *X, cons
             rc = launch_hidden_backward(n, wi, wo, T, WT, Hl[l], dPrev, io->dW[l], scratch, stream);
             if (rc == AG_ERR_UNSUPPORTED) {
                 if ((rc = launch_gemm_tn(n, wi, wo, Hl[l], T, io->dW[l], nullptr, scratch, stream))) return rc;
-                rc = launch_gemm_nn(n, wo, wi, T, WT, dPrev, 2, Hl[l], stream);
+                rc = launch_gemm_nn_auto(n, wo, wi, T, WT, dPrev, 2, Hl[l], wsplit, stream);
             }
             if (rc) return rc;
         } else {
@@ -173,7 +176,7 @@ int ag_gin_step(ag_plan *const *plans, const ag_gin_io *io, const float *X, cons
             if ((rc = ag_gin_layer_t(plans[l + 1], eps, dPre, T, stream))) return rc;                 // T = A^T dPre
             if ((rc = launch_transpose_small(wi, wo, io->W[l], WT, stream))) return rc;
             // dPre_{l-1} = (T W_l^T) masked by H_l > 0
-            if ((rc = launch_gemm_nn(n, wo, wi, T, WT, dPrev, 2, Hl[l], stream))) return rc;
+            if ((rc = launch_gemm_nn_auto(n, wo, wi, T, WT, dPrev, 2, Hl[l], wsplit, stream))) return rc;
         }
         dPre = dPrev;
     }

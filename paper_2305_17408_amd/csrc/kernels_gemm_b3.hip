@@ -1,0 +1,224 @@
+// Layer transform C[N x n] = epilogue(A[N x k] W[k x n]) on the bf16 matrix instruction at fp32
+// accuracy (the dense Update of paper Sec. 2.1; mixed precision is the direction Sec. 3.2 names
+// as future work, here without giving up accuracy).
+//
+// Every fp32 operand is cut into three bf16 pieces that add up to it exactly (8 + 8 + 8 mantissa
+// bits, by truncation with the remainder computed exactly).  Of the nine piece products the six
+// with weight >= 2^-16 are accumulated in fp32, smallest first:
+//     a b ~= a3 b1 + a1 b3 + a2 b2 + a2 b1 + a1 b2 + a1 b1      (dropped terms <= 2^-23 |a b|)
+// which is the accuracy of an fp32 multiply-add chain, at 6/16 of the fp32 matrix-pipe time.
+// W is split once by a small kernel into K-contiguous piece rows; A is split while its tile is
+// staged into LDS.  Operand layout of v_mfma_f32_32x32x16_bf16 for lane l: A[l & 31][8 (l >> 5) +
+// 0..7], B[8 (l >> 5) + 0..7][l & 31]; result register r holds D[8 (r / 4) + 4 (l >> 5) + (r & 3)][l & 31].
+#include "kernels_common.h"
+
+namespace ag {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // 16 bytes of packed bf16 pieces
+
+enum { EPI_NONE = 0, EPI_BIAS_RELU = 1, EPI_RELU_MASK = 2 };
+
+constexpr int kStage = 32;              // k values staged per step (two matrix instructions deep)
+constexpr int kRowB = kStage * 2 + 16;  // bytes per LDS operand row: 64 of data + 16 of padding, so
+                                        // the eight lanes of a 16-byte read phase hit distinct banks
+
+__device__ __forceinline__ floatx16 mfma16(const u32x4 &a, const u32x4 &b, const floatx16 &c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ void cut3(float h, uint32_t (&p)[3])
+{
+    p[0] = __float_as_uint(h) & 0xffff0000u;
+    const float r1 = h - __uint_as_float(p[0]);
+    p[1] = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(p[1]);
+    p[2] = __float_as_uint(r2) & 0xffff0000u;
+}
+
+// Wp[(piece * npad + col) * kpad + kk] = piece of W[kk][col]; zero for kk >= k or col >= n
+__global__ __launch_bounds__(kWG) void k_split_w(const float *__restrict__ W, uint16_t *__restrict__ Wp,
+                                                 int k, int kpad, int n, int npad)
+{
+    const int64_t i = (int64_t)blockIdx.x * kWG + threadIdx.x;
+    if (i >= (int64_t)kpad * npad) return;
+    const int kk = (int)(i / npad), col = (int)(i % npad);
+    uint32_t p[3] = {0u, 0u, 0u};
+    if (kk < k && col < n) cut3(W[(size_t)kk * n + col], p);
+#pragma unroll
+    for (int s = 0; s < 3; ++s) Wp[((size_t)s * npad + col) * kpad + kk] = (uint16_t)(p[s] >> 16);
+}
+
+// WVM x 2 wavefronts, each owning WM x WN tiles of 32 x 32.  Work-groups that share rows of A (the
+// column tiles of one row tile) have neighbouring ids, so the second read of those rows is served
+// by the memory-side cache.
+template <int WVM, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WVM * 128) void k_gemm_nn_b3(const float *__restrict__ A, const uint16_t *__restrict__ Wp,
+                                                      float *__restrict__ C, int64_t N, int k, int kpad, int n,
+                                                      int npad, int ncol_tiles, const float *__restrict__ aux)
+{
+    constexpr int kWG = WVM * 128;                            // threads of this kernel's work-group
+    constexpr int TM = WVM * WM * 32, TN = 2 * WN * 32;
+    constexpr int UA = TM * kStage / 4 / kWG;                 // float4 loads of A per thread and stage
+    constexpr int NW = 3 * TN * kStage / 8;                   // 16-byte units of the W pieces per stage
+    constexpr int UW = (NW + kWG - 1) / kWG;                  // ... per thread
+    static_assert(TM * kStage / 4 % kWG == 0, "tile must divide among the threads");
+    __shared__ __attribute__((aligned(16))) unsigned char sA[3 * TM * kRowB];
+    __shared__ __attribute__((aligned(16))) unsigned char sW[3 * TN * kRowB];
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    const int wm = w >> 1, wn = w & 1;
+    const int64_t r0 = (int64_t)(blockIdx.x / ncol_tiles) * TM;
+    const int n0 = (blockIdx.x % ncol_tiles) * TN;
+
+    floatx16 acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    float4 ra[UA];
+    u32x4 rw[UW];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * kWG, r = idx / (kStage / 4), c = (idx % (kStage / 4)) * 4;
+            ra[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r0 + r < N && k0 + c < k) ra[u] = *reinterpret_cast<const float4 *>(A + (r0 + r) * k + k0 + c);
+        }
+#pragma unroll
+        for (int u = 0; u < UW; ++u) {
+            const int idx = tid + u * kWG, pc = idx / (TN * kStage / 8), rem = idx % (TN * kStage / 8);
+            const int col = rem / (kStage / 8), c = (rem % (kStage / 8)) * 8;
+            rw[u] = u32x4{0u, 0u, 0u, 0u};
+            if (idx < NW) rw[u] = *reinterpret_cast<const u32x4 *>(Wp + ((size_t)pc * npad + n0 + col) * kpad + k0 + c);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * kWG, r = idx / (kStage / 4), c = (idx % (kStage / 4)) * 4;
+            uint32_t px[3], py[3], pz[3], pw[3];
+            cut3(ra[u].x, px); cut3(ra[u].y, py); cut3(ra[u].z, pz); cut3(ra[u].w, pw);
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                *reinterpret_cast<uint2 *>(sA + (s * TM + r) * kRowB + c * 2) =
+                    make_uint2((px[s] >> 16) | py[s], (pz[s] >> 16) | pw[s]);
+        }
+#pragma unroll
+        for (int u = 0; u < UW; ++u) {
+            const int idx = tid + u * kWG, pc = idx / (TN * kStage / 8), rem = idx % (TN * kStage / 8);
+            const int col = rem / (kStage / 8), c = (rem % (kStage / 8)) * 8;
+            if (idx < NW) *reinterpret_cast<u32x4 *>(sW + (pc * TN + col) * kRowB + c * 2) = rw[u];
+        }
+    };
+
+    fetch(0);
+    for (int k0 = 0; k0 < kpad; k0 += kStage) {
+        __syncthreads();                       // everyone is done reading the previous tiles
+        stash();
+        __syncthreads();
+        if (k0 + kStage < kpad) fetch(k0 + kStage);
+#pragma unroll
+        for (int ks = 0; ks < kStage / 16; ++ks) {
+            u32x4 a[WM][3], b[WN][3];
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    a[i][s] = *reinterpret_cast<const u32x4 *>(
+                        sA + (s * TM + (wm * WM + i) * 32 + lo) * kRowB + (ks * 16 + 8 * hi) * 2);
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    b[j][s] = *reinterpret_cast<const u32x4 *>(
+                        sW + (s * TN + (wn * WN + j) * 32 + lo) * kRowB + (ks * 16 + 8 * hi) * 2);
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j) {
+                    floatx16 c = acc[i][j];
+                    c = mfma16(a[i][2], b[j][0], c);
+                    c = mfma16(a[i][0], b[j][2], c);
+                    c = mfma16(a[i][1], b[j][1], c);
+                    c = mfma16(a[i][1], b[j][0], c);
+                    c = mfma16(a[i][0], b[j][1], c);
+                    c = mfma16(a[i][0], b[j][0], c);
+                    acc[i][j] = c;
+                }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int col = n0 + (wn * WN + j) * 32 + lo;
+            if (col >= n) continue;
+            float bias = 0.f;
+            if constexpr (EPI == EPI_BIAS_RELU) bias = aux[col];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = r0 + (wm * WM + i) * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
+                if (row >= N) continue;
+                float v = acc[i][j][r];
+                if constexpr (EPI == EPI_BIAS_RELU) v = fmaxf(v + bias, 0.f);
+                if constexpr (EPI == EPI_RELU_MASK) v = (aux[row * n + col] > 0.f) ? v : 0.f;
+                C[row * n + col] = v;
+            }
+        }
+}
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+template <int EPI>
+void run_b3(int64_t N, int k, int n, const float *A, const uint16_t *Wp, float *C, const float *aux, hipStream_t st)
+{
+    const int kpad = round_up(k, kStage), npad = round_up(n, 128);
+    const int ct = npad / 128;
+    dim3 grid((unsigned)(((N + 127) / 128) * ct));
+    hipLaunchKernelGGL((k_gemm_nn_b3<4, 1, 2, EPI>), grid, dim3(512), 0, st, A, Wp, C, N, k, kpad, n, npad, ct, aux);
+}
+
+}  // namespace
+
+// floats of scratch the split copy of W needs (0 if the shape is not served by this path: narrow
+// outputs are bound by memory, not by the matrix pipe, and stay on the fp32 kernels)
+size_t gemm_nn_b3_scratch_floats(int32_t k, int32_t n)
+{
+    if (k < 32 || k % 4 || n <= 64) return 0;
+    return ((size_t)3 * round_up(n, 128) * round_up(k, kStage) * sizeof(uint16_t) + 3) / 4 + 4;
+}
+
+// Returns AG_ERR_UNSUPPORTED when the shape is not served here (the caller then uses the fp32 kernels).
+int launch_gemm_nn_b3(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
+                      const float *aux, float *wsplit, void *stream)
+{
+    if (!wsplit || gemm_nn_b3_scratch_floats(k, n) == 0) return AG_ERR_UNSUPPORTED;
+    if (N <= 0) return AG_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int kpad = round_up(k, kStage), npad = round_up(n, 128);
+    uint16_t *Wp = reinterpret_cast<uint16_t *>(wsplit);
+    const int64_t cells = (int64_t)kpad * npad;
+    hipLaunchKernelGGL(k_split_w, dim3((unsigned)((cells + kWG - 1) / kWG)), dim3(kWG), 0, st, W, Wp, k, kpad, n, npad);
+    if (epilogue == EPI_BIAS_RELU) run_b3<EPI_BIAS_RELU>(N, k, n, A, Wp, C, aux, st);
+    else if (epilogue == EPI_RELU_MASK) run_b3<EPI_RELU_MASK>(N, k, n, A, Wp, C, aux, st);
+    else run_b3<EPI_NONE>(N, k, n, A, Wp, C, aux, st);
+    return hip_fail((int)hipGetLastError(), "gemm_nn_b3 launch");
+}
+
+// The layer transform on the fastest path that serves the shape: bf16 pieces when `wsplit` (at least
+// gemm_nn_b3_scratch_floats(k, n) floats) is given and the shape fits, else the fp32 kernels.
+int launch_gemm_nn_auto(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
+                        const float *aux, float *wsplit, void *stream)
+{
+    const int rc = launch_gemm_nn_b3(N, k, n, A, W, C, epilogue, aux, wsplit, stream);
+    if (rc != AG_ERR_UNSUPPORTED) return rc;
+    return launch_gemm_nn(N, k, n, A, W, C, epilogue, aux, stream);
+}
+
+}  // namespace ag

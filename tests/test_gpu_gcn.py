@@ -61,6 +61,15 @@ def test_gcn_step_small_nonsymmetric():
     compare(got, ref, perm)
 
 
+@pytest.mark.parametrize("dims", [(36, 200, 8), (128, 72, 5), (64, 136, 16)])
+def test_gcn_step_ragged_widths(dims):
+    # widths that are not multiples of the GEMM tiles (the wide transforms run on bf16 pieces, the
+    # narrow ones on fp32 MFMA), vertex count not a multiple of 128
+    g = row_normalise(planted_partition(13, 50, 8, 0.7, 8))
+    got, ref, perm = run_step(g, *dims)
+    compare(got, ref, perm)
+
+
 def test_gcn_step_config3_shape_scaled():
     g = config_graph(3, scale=1 / 64)
     got, ref, perm = run_step(g, 128, 256, 16)
