@@ -10,6 +10,8 @@
 // W is split once by a small kernel into K-contiguous piece rows; A is split while its tile is
 // staged into LDS.  Operand layout of v_mfma_f32_32x32x16_bf16 for lane l: A[l & 31][8 (l >> 5) +
 // 0..7], B[8 (l >> 5) + 0..7][l & 31]; result register r holds D[8 (r / 4) + 4 (l >> 5) + (r & 3)][l & 31].
+#include <algorithm>
+
 #include "kernels_common.h"
 
 namespace ag {
@@ -52,16 +54,16 @@ __global__ __launch_bounds__(kWG) void k_split_w(const float *__restrict__ W, ui
     for (int s = 0; s < 3; ++s) Wp[((size_t)s * npad + col) * kpad + kk] = (uint16_t)(p[s] >> 16);
 }
 
-// WVM x 2 wavefronts, each owning WM x WN tiles of 32 x 32.  Work-groups that share rows of A (the
+// WVM x WVN wavefronts, each owning WM x WN tiles of 32 x 32.  Work-groups that share rows of A (the
 // column tiles of one row tile) have neighbouring ids, so the second read of those rows is served
 // by the memory-side cache.
-template <int WVM, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WVM * 128) void k_gemm_nn_b3(const float *__restrict__ A, const uint16_t *__restrict__ Wp,
+template <int WVM, int WVN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WVM * WVN * 64) void k_gemm_nn_b3(const float *__restrict__ A, const uint16_t *__restrict__ Wp,
                                                       float *__restrict__ C, int64_t N, int k, int kpad, int n,
                                                       int npad, int ncol_tiles, const float *__restrict__ aux)
 {
-    constexpr int kWG = WVM * 128;                            // threads of this kernel's work-group
-    constexpr int TM = WVM * WM * 32, TN = 2 * WN * 32;
+    constexpr int kWG = WVM * WVN * 64;                       // threads of this kernel's work-group
+    constexpr int TM = WVM * WM * 32, TN = WVN * WN * 32;
     constexpr int UA = TM * kStage / 4 / kWG;                 // float4 loads of A per thread and stage
     constexpr int NW = 3 * TN * kStage / 8;                   // 16-byte units of the W pieces per stage
     constexpr int UW = (NW + kWG - 1) / kWG;                  // ... per thread
@@ -69,21 +71,17 @@ __global__ __launch_bounds__(WVM * 128) void k_gemm_nn_b3(const float *__restric
     __shared__ __attribute__((aligned(16))) unsigned char sA[3 * TM * kRowB];
     __shared__ __attribute__((aligned(16))) unsigned char sW[3 * TN * kRowB];
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
-    const int wm = w >> 1, wn = w & 1;
-    const int64_t r0 = (int64_t)(blockIdx.x / ncol_tiles) * TM;
-    const int n0 = (blockIdx.x % ncol_tiles) * TN;
-
-    floatx16 acc[WM][WN];
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const int wm = w / WVN, wn = w % WVN;
+    // Persistent work-groups: each walks the output tiles t, t + gridDim.x, ...; the loads of the
+    // next stage are always in flight during the current one, also across the end of a tile, so
+    // a tile's first memory latency and its write-out overlap with its neighbours' work.
+    const int64_t ntiles = ((N + TM - 1) / TM) * ncol_tiles;
 
     float4 ra[UA];
     u32x4 rw[UW];
-    auto fetch = [&](int k0) {
+    auto fetch = [&](int64_t tile, int k0) {
+        const int64_t r0 = (tile / ncol_tiles) * TM;
+        const int n0 = (int)(tile % ncol_tiles) * TN;
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
             const int idx = tid + u * kWG, r = idx / (kStage / 4), c = (idx % (kStage / 4)) * 4;
@@ -117,12 +115,23 @@ __global__ __launch_bounds__(WVM * 128) void k_gemm_nn_b3(const float *__restric
         }
     };
 
-    fetch(0);
+    fetch(blockIdx.x, 0);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int64_t r0 = (tile / ncol_tiles) * TM;
+    const int n0 = (int)(tile % ncol_tiles) * TN;
+    floatx16 acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     for (int k0 = 0; k0 < kpad; k0 += kStage) {
         __syncthreads();                       // everyone is done reading the previous tiles
         stash();
         __syncthreads();
-        if (k0 + kStage < kpad) fetch(k0 + kStage);
+        if (k0 + kStage < kpad) fetch(tile, k0 + kStage);
+        else if (tile + gridDim.x < ntiles) fetch(tile + gridDim.x, 0);
 #pragma unroll
         for (int ks = 0; ks < kStage / 16; ++ks) {
             u32x4 a[WM][3], b[WN][3];
@@ -171,6 +180,7 @@ __global__ __launch_bounds__(WVM * 128) void k_gemm_nn_b3(const float *__restric
                 C[row * n + col] = v;
             }
         }
+    }
 }
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
@@ -178,10 +188,16 @@ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 template <int EPI>
 void run_b3(int64_t N, int k, int n, const float *A, const uint16_t *Wp, float *C, const float *aux, hipStream_t st)
 {
-    const int kpad = round_up(k, kStage), npad = round_up(n, 128);
-    const int ct = npad / 128;
-    dim3 grid((unsigned)(((N + 127) / 128) * ct));
-    hipLaunchKernelGGL((k_gemm_nn_b3<4, 1, 2, EPI>), grid, dim3(512), 0, st, A, Wp, C, N, k, kpad, n, npad, ct, aux);
+    const int kpad = round_up(k, kStage), npad = round_up(n, 256);
+    if (n > 128) {
+        // 128 x 256 tile, 16 waves: a row tile of A is staged (and cut) once for 256 output columns
+        const int ct = (n + 255) / 256;
+        dim3 grid((unsigned)std::min<int64_t>(((N + 127) / 128) * ct, 256));
+        hipLaunchKernelGGL((k_gemm_nn_b3<4, 4, 1, 2, EPI>), grid, dim3(1024), 0, st, A, Wp, C, N, k, kpad, n, npad, ct, aux);
+    } else {
+        dim3 grid((unsigned)std::min<int64_t>((N + 127) / 128, 512));
+        hipLaunchKernelGGL((k_gemm_nn_b3<4, 2, 1, 2, EPI>), grid, dim3(512), 0, st, A, Wp, C, N, k, kpad, n, npad, 1, aux);
+    }
 }
 
 }  // namespace
@@ -191,7 +207,7 @@ void run_b3(int64_t N, int k, int n, const float *A, const uint16_t *Wp, float *
 size_t gemm_nn_b3_scratch_floats(int32_t k, int32_t n)
 {
     if (k < 32 || k % 4 || n <= 64) return 0;
-    return ((size_t)3 * round_up(n, 128) * round_up(k, kStage) * sizeof(uint16_t) + 3) / 4 + 4;
+    return ((size_t)3 * round_up(n, 256) * round_up(k, kStage) * sizeof(uint16_t) + 3) / 4 + 4;
 }
 
 // Returns AG_ERR_UNSUPPORTED when the shape is not served here (the caller then uses the fp32 kernels).
@@ -201,7 +217,7 @@ int launch_gemm_nn_b3(int64_t N, int32_t k, int32_t n, const float *A, const flo
     if (!wsplit || gemm_nn_b3_scratch_floats(k, n) == 0) return AG_ERR_UNSUPPORTED;
     if (N <= 0) return AG_OK;
     hipStream_t st = (hipStream_t)stream;
-    const int kpad = round_up(k, kStage), npad = round_up(n, 128);
+    const int kpad = round_up(k, kStage), npad = round_up(n, 256);
     uint16_t *Wp = reinterpret_cast<uint16_t *>(wsplit);
     const int64_t cells = (int64_t)kpad * npad;
     hipLaunchKernelGGL(k_split_w, dim3((unsigned)((cells + kWG - 1) / kWG)), dim3(kWG), 0, st, W, Wp, k, kpad, n, npad);
