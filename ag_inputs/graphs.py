@@ -92,7 +92,8 @@ def gcn_normalise(g: Graph) -> Graph:
     inv = 1.0 / np.sqrt(deg)
     rows = np.repeat(np.arange(g.n, dtype=np.int64), np.diff(g.rowptr))
     vals = (inv[rows] * inv[g.colidx]).astype(np.float32)
-    return Graph(g.n, g.rowptr, g.colidx, vals, dict(g.meta, norm="gcn"))
+    scale = inv.astype(np.float32)                       # vals[i][j] ~ scale[i] * scale[j]
+    return Graph(g.n, g.rowptr, g.colidx, vals, dict(g.meta, norm="gcn", row_scale=scale, col_scale=scale))
 
 
 def row_normalise(g: Graph) -> Graph:
@@ -101,7 +102,8 @@ def row_normalise(g: Graph) -> Graph:
     deg[deg == 0] = 1.0
     rows = np.repeat(np.arange(g.n, dtype=np.int64), np.diff(g.rowptr))
     vals = (1.0 / deg[rows]).astype(np.float32)
-    return Graph(g.n, g.rowptr, g.colidx, vals, dict(g.meta, norm="row"))
+    return Graph(g.n, g.rowptr, g.colidx, vals, dict(g.meta, norm="row", row_scale=(1.0 / deg).astype(np.float32),
+                                                     col_scale=None))
 
 
 # --------------------------------------------------------------------------- #

@@ -82,6 +82,15 @@ typedef struct {
     void *(*dev_alloc)(size_t bytes, void *user);   /* default hipMalloc                       */
     void  (*dev_free)(void *ptr, void *user);       /* default hipFree                         */
     void   *user;
+    /* Factored values (optional, host arrays of n floats, borrowed during ag_plan_create): a     *
+     * declaration that vals[i][j] = row_scale[i] * col_scale[j] up to fp32 rounding, a missing   *
+     * array counting as all ones: D^-1/2 on both sides for the GCN normalisation, D^-1 as        *
+     * row_scale for aggregate-mean (Sec. 2.1).  The diagonal blocks then run value-free: the     *
+     * pattern kernels (the bit-map dense kernels of Sec. 3.2 included) with col_scale applied to  *
+     * the feature rows on the way in and row_scale to the sums on the way out; the remainder     *
+     * keeps the stored values.  Needs vals; AG_ERR_INVALID if an intra-community value departs   *
+     * from the product by more than 1e-6 relative.                                               */
+    const float *row_scale, *col_scale;
 } ag_options;
 
 /* ---- plan life cycle -------------------------------------------------------------------- */
@@ -125,7 +134,7 @@ int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int3
 #define AG_K_BLOCK_DENSE      1   /* dense tile on fp32 MFMA (Sec. 3.2, dense-based kernel)       */
 #define AG_K_BLOCK_DENSE_BF16X3 2 /* the same on bf16 MFMA at fp32 accuracy: features cut into     *
                                    * three bf16 pieces that sum to them exactly; unit-weight        *
-                                   * matrices only (AG_ERR_UNSUPPORTED otherwise)                   */
+                                   * or factored matrices only (AG_ERR_UNSUPPORTED otherwise)       */
 /* kernels for the remainder: lanes cooperating on one row */
 #define AG_K_CSR_NARROW       0   /* one feature-wide lane group per row (Sec. 3.2, CSR inter)    */
 #define AG_K_CSR_WIDE         1   /* several lane groups per row, neighbours interleaved          */
@@ -205,6 +214,7 @@ typedef struct {
     /* the dense class on its own (forward direction): its rows, its intra-community entries and *
      * the remainder entries of its rows; and the remainder entries of all block rows            */
     int64_t dense_rows, nnz_intra_dense, nnz_inter_dense_rows, nnz_inter_block_rows;
+    int32_t factored;                          /* row_scale / col_scale in use (value-free blocks) */
 } ag_stats;
 
 int ag_plan_stats(const ag_plan *p, ag_stats *out);

@@ -43,7 +43,8 @@ class ag_options(C.Structure):
                 ("max_levels", C.c_int32), ("order_levels", C.c_int32), ("trials", C.c_int32),
                 ("layout", C.c_int32),
                 ("flags", C.c_int32), ("dense_density", C.c_float),
-                ("dev_alloc", C.c_void_p), ("dev_free", C.c_void_p), ("user", C.c_void_p)]
+                ("dev_alloc", C.c_void_p), ("dev_free", C.c_void_p), ("user", C.c_void_p),
+                ("row_scale", C.c_void_p), ("col_scale", C.c_void_p)]
 
 
 class ag_selector_info(C.Structure):
@@ -69,7 +70,8 @@ class ag_stats(C.Structure):
                 ("sec_upload", C.c_double), ("device_bytes", C.c_int64),
                 ("block_density_hist", C.c_int32 * 8),
                 ("dense_rows", C.c_int64), ("nnz_intra_dense", C.c_int64),
-                ("nnz_inter_dense_rows", C.c_int64), ("nnz_inter_block_rows", C.c_int64)]
+                ("nnz_inter_dense_rows", C.c_int64), ("nnz_inter_block_rows", C.c_int64),
+                ("factored", C.c_int32)]
 
 
 class ag_profile(C.Structure):
@@ -187,9 +189,18 @@ def ag_plan_create(rowptr, colidx, vals, N: int, F: int, **options):
     a = ag_csr(int(rowptr.size - 1), int(colidx.size), rowptr.ctypes.data_as(_i32p),
                colidx.ctypes.data_as(_i32p), None if vals is None else vals.ctypes.data_as(_f32p))
     o = ag_options()
+    keep = []                                            # host arrays borrowed by the call
     for k, v in options.items():
         if not hasattr(o, k):
             raise TypeError(f"unknown option {k}")
+        if k in ("row_scale", "col_scale"):
+            if v is None:
+                continue
+            v = np.ascontiguousarray(v, dtype=np.float32)
+            if v.size != int(N):
+                raise ValueError(f"{k} must have N entries")
+            keep.append(v)
+            v = v.ctypes.data
         setattr(o, k, v)
     out = C.c_void_p()
     _check(lib().ag_plan_create(C.byref(a), int(N), int(F), C.byref(o), C.byref(out)))

@@ -89,6 +89,9 @@ struct BlocksDev {
     int32_t n_dense = 0, n_sparse = 0;
     const uint32_t *bitmap = nullptr;      // n_dense x 128 x 4
     const float    *tiles = nullptr;       // n_dense x 16384, nullptr = unit weights
+    // factored values: feature rows are multiplied by in_scale[row] when staged, a row's sum over its
+    // block entries by out_scale[row] (plan numbering; nullptr = 1)
+    const float *in_scale = nullptr, *out_scale = nullptr;
 };
 
 struct DevDir {

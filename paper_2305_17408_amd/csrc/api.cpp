@@ -3,6 +3,7 @@
 
 #include <algorithm>
 #include <chrono>
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 
@@ -42,6 +43,9 @@ struct Topology {
     ag_options opt{};
     int64_t n = 0, nnz = 0;
     bool unit = false, symmetric = false, host_only = false;
+    bool factored = false;              // intra-community values are row_scale[i] * col_scale[j]: blocks run value-free
+    std::vector<float> rs_plan, cs_plan;   // the factors in plan numbering (empty = all ones)
+    const float *rs_dev = nullptr, *cs_dev = nullptr;
     ReorderResult r;
     HostDir h[2];                       // h[1] is filled only for non-symmetric matrices
     std::vector<int32_t> dense_blocks, sparse_blocks, all_blocks;
@@ -120,12 +124,15 @@ struct Topology {
         std::vector<int32_t> irp(H.intra.rowptr.begin(), H.intra.rowptr.begin() + B.n_block_rows + 1);
         if ((rc = upload(irp, B.i_rowptr))) return rc;
         if ((rc = upload(H.intra_col8, B.i_col8))) return rc;
-        if (!H.intra.val.empty()) { if ((rc = upload(H.intra.val, B.i_val))) return rc; }
+        if (!H.intra.val.empty() && !factored) { if ((rc = upload(H.intra.val, B.i_val))) return rc; }
         B.list_dense = ld; B.list_sparse = ls; B.list_all = la;
         B.n_dense = (int32_t)dense_blocks.size();
         B.n_sparse = (int32_t)sparse_blocks.size();
         if ((rc = upload(H.bitmap, B.bitmap))) return rc;
-        if (!unit && B.n_dense > 0) { if ((rc = upload(H.tiles, B.tiles))) return rc; }
+        if (!unit && !factored && B.n_dense > 0) { if ((rc = upload(H.tiles, B.tiles))) return rc; }
+        // A = diag(rs) P diag(cs): forward scales sources by cs and sums by rs; A^T the other way round
+        B.in_scale = (k == 0) ? cs_dev : rs_dev;
+        B.out_scale = (k == 0) ? rs_dev : cs_dev;
         return AG_OK;
     }
 };
@@ -200,7 +207,7 @@ void init_selector(ag_plan *p, int dir, bool keep_forced)
     Selector &s = p->sel[dir];
     s.reset(keep_forced);
     const Topology &t = *p->topo;
-    s.ncand[AG_CLS_BLOCKS_DENSE] = t.dense_blocks.empty() ? 1 : (t.unit ? 3 : 2);
+    s.ncand[AG_CLS_BLOCKS_DENSE] = t.dense_blocks.empty() ? 1 : ((t.unit || t.factored) ? 3 : 2);
     s.ncand[AG_CLS_BLOCKS_SPARSE] = 1;
     s.ncand[AG_CLS_REMAINDER] = 3;
     s.ncand[AG_CLS_COMPOSE] = 4;
@@ -489,8 +496,13 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
         t->n = A0.n;
         t->nnz = A0.nnz();
         t->unit = A0.val.empty();
-        // the bf16 dense kernel (unit weights) overtakes the block-sparse kernel at far lower densities
-        if (o.dense_density == 0.f) o.dense_density = t->opt.dense_density = t->unit ? 0.05f : 0.20f;
+        const bool want_factored = o.row_scale || o.col_scale;
+        if (want_factored && t->unit) {
+            set_error("row_scale / col_scale describe stored values: vals is required");
+            return AG_ERR_INVALID;
+        }
+        // the value-free dense kernels (bit maps, bf16 form) overtake the block-sparse kernel at far lower densities
+        if (o.dense_density == 0.f) o.dense_density = t->opt.dense_density = (t->unit || want_factored) ? 0.05f : 0.20f;
         double t0 = now_sec();
         transpose_csr(A0, At);
         t->symmetric = bitwise_equal(A0, At);
@@ -504,6 +516,24 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
         t->sec_reorder = t1 - t0;
         permute_and_split(A0, t->r, t->h[0].full, t->h[0].intra, t->h[0].inter);
         if (!t->symmetric) permute_and_split(At, t->r, t->h[1].full, t->h[1].intra, t->h[1].inter);
+        if (want_factored) {
+            // factors in plan numbering; every intra-community value must be their product
+            const int64_t n = t->n;
+            if (o.row_scale) { t->rs_plan.resize(n); for (int64_t q = 0; q < n; ++q) t->rs_plan[q] = o.row_scale[t->r.perm[q]]; }
+            if (o.col_scale) { t->cs_plan.resize(n); for (int64_t q = 0; q < n; ++q) t->cs_plan[q] = o.col_scale[t->r.perm[q]]; }
+            const HostCsr &I0 = t->h[0].intra;
+            for (int64_t i = 0; i < n; ++i)
+                for (int32_t e = I0.rowptr[i]; e < I0.rowptr[i + 1]; ++e) {
+                    const float prod = (o.row_scale ? t->rs_plan[i] : 1.f) * (o.col_scale ? t->cs_plan[I0.col[e]] : 1.f);
+                    const float v = I0.val[e];
+                    if (!(std::fabs(v - prod) <= 1e-6f * std::fabs(v))) {
+                        set_error("a stored value is not row_scale[i] * col_scale[j]");
+                        return AG_ERR_INVALID;
+                    }
+                }
+            t->factored = true;
+        }
+        t->opt.row_scale = t->opt.col_scale = nullptr;        // borrowed pointers are not kept
         double t2 = now_sec();
         t->sec_split = t2 - t1;
         // density classes (decided on the forward matrix; the transpose has the same counts)
@@ -519,7 +549,7 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
         for (int k = 0; k < ndir; ++k) {
             build_segments(t->h[k].full, t->h[k].segs_full);
             build_segments(t->h[k].inter, t->h[k].segs_inter);
-            build_block_formats(t->r, t->dense_blocks, t->unit, t->h[k]);
+            build_block_formats(t->r, t->dense_blocks, t->unit || t->factored, t->h[k]);
         }
         double t3 = now_sec();
         t->sec_build = t3 - t2;
@@ -530,6 +560,8 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
             if ((rc = t->upload(t->sparse_blocks, ls))) return rc;
             if ((rc = t->upload(t->all_blocks, la))) return rc;
             if ((rc = t->upload(t->r.perm, t->perm_dev))) return rc;
+            if (!t->rs_plan.empty()) { if ((rc = t->upload(t->rs_plan, t->rs_dev))) return rc; }
+            if (!t->cs_plan.empty()) { if ((rc = t->upload(t->cs_plan, t->cs_dev))) return rc; }
             for (int k = 0; k < ndir; ++k)
                 if ((rc = t->upload_dir(k, bp, ld, ls, la))) return rc;
             if ((rc = hip_fail((int)hipDeviceSynchronize(), "upload sync"))) return rc;
@@ -604,8 +636,8 @@ int ag_plan_force_kernels(ag_plan *p, int32_t cls, int32_t dir, int32_t kernel_i
     static const int limit[AG_NUM_CLS] = {3, 1, 3, 4};
     if (kernel_id < -1 || kernel_id >= 4) { set_error("kernel id out of range"); return AG_ERR_INVALID; }
     if (kernel_id >= limit[cls]) { set_error("kernel id not available for this class"); return AG_ERR_UNSUPPORTED; }
-    if (cls == AG_CLS_BLOCKS_DENSE && kernel_id == AG_K_BLOCK_DENSE_BF16X3 && !p->topo->unit) {
-        set_error("the bf16x3 dense kernel takes unit-weight matrices only");
+    if (cls == AG_CLS_BLOCKS_DENSE && kernel_id == AG_K_BLOCK_DENSE_BF16X3 && !p->topo->unit && !p->topo->factored) {
+        set_error("the bf16x3 dense kernel takes unit-weight or factored matrices only");
         return AG_ERR_UNSUPPORTED;
     }
     Selector &s = p->sel[dir];
@@ -717,6 +749,7 @@ int ag_plan_stats(const ag_plan *p, ag_stats *out)
         out->nnz_inter_dense_rows += O.rowptr[r1] - O.rowptr[r0];
     }
     out->nnz_inter_block_rows = O.rowptr[out->n_block_rows];
+    out->factored = t.factored;
     out->density_full = nn > 0 ? (double)t.nnz / nn : 0;
     out->density_intra = blk_area > 0 ? (double)out->nnz_intra / blk_area : 0;
     out->density_inter = nn - blk_area > 0 ? (double)out->nnz_inter / (nn - blk_area) : 0;

@@ -74,6 +74,8 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
     const int first = min(team * rpt, nr);
     const int myrows = min(rpt, nr - first);
     const int irp = B.i_rowptr[r0 + first + min(gl, myrows)];
+    // factored values: lane gl keeps the output factor of the team's row gl (fetched with the row pointers)
+    const float osc = (B.out_scale && gl < myrows) ? B.out_scale[r0 + first + gl] : 1.f;
     const int ie1 = __shfl(irp, myrows, G);
     int iq = __shfl(irp, 0, G);                         // entry held by lane 0 of ring chunk 0
     int ic0, ic1, ic2;
@@ -107,7 +109,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
         ld_r(rq + G + gl, rc1, rv1);
         ld_r(rq + 2 * G + gl, rc2, rv2);
     }
-    stage_tile<FT, VEC>(H, F, r0, nr, nr, f0, sH, tid);
+    stage_tile<FT, VEC>(H, F, r0, nr, nr, f0, sH, tid, B.in_scale);
     for (int j = tid; j < FT; j += kWG) sH[kMaxBlock * FT + j] = 0.f;
     __syncthreads();
     for (int i = 0; i < myrows; ++i) {
@@ -130,6 +132,13 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
                 chunk_range_lds<G, NV, VEC>(ic0, iv0, k - iq, hi, sH, gl, acc);
                 k = iq + hi;
             }
+        }
+        if (B.out_scale) {                              // factored values: the row's factor on its block sum
+            const float sc = __shfl(osc, i, G);
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[q][j] *= sc;
         }
         if constexpr (FUSED) {
             const int rb = __shfl(rrp, i, G), re = __shfl(rrp, i + 1, G);

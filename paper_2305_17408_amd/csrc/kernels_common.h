@@ -52,10 +52,11 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
 // Copy rows [r0, r0+nr) x columns [f0, f0+FT) of the row-major matrix H (F columns) into the LDS
 // tile sH[row][FT]; rows nr..pad_rows-1 and columns beyond F are zero-filled.  All loads of a
 // thread are issued before its first LDS store, so a tile costs one memory latency, not one per
-// row.  Must be called by the whole work-group; the caller synchronises afterwards.
+// row.  With `scale` every row is multiplied by scale[row] on the way (factored edge values).
+// Must be called by the whole work-group; the caller synchronises afterwards.
 template <int FT, int VEC>
 __device__ __forceinline__ void stage_tile(const float *__restrict__ H, int F, int r0, int nr, int pad_rows,
-                                           int f0, float *sH, int tid)
+                                           int f0, float *sH, int tid, const float *__restrict__ scale = nullptr)
 {
     constexpr int UPR = FT / VEC;                       // load units per tile row
     constexpr int ITER = (kMaxBlock * UPR + kWG - 1) / kWG;
@@ -65,6 +66,11 @@ __device__ __forceinline__ void stage_tile(const float *__restrict__ H, int F, i
         const int idx = tid + it * kWG, r = idx / UPR, ff = f0 + (idx % UPR) * VEC;
         if (r < nr && ff < F) {
             load_vec<VEC>(H + (size_t)(r0 + r) * F + ff, h[it]);
+            if (scale) {
+                const float sc = scale[r0 + r];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) h[it][j] *= sc;
+            }
         } else {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) h[it][j] = 0.f;

@@ -26,10 +26,17 @@ template <int NT, int VEC, bool FUSED>
 __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_has_rows, float *sOut,
                                           RemainderRows<32 * NT, VEC> &rem, const CsrDev &R,
                                           const float *__restrict__ H, float *__restrict__ Y,
-                                          int F, int r0, int nr, int f0, int tid)
+                                          int F, int r0, int nr, int f0, int tid,
+                                          const float *__restrict__ out_scale)
 {
     constexpr int FT = 32 * NT;
     const int w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    float osc[16];                                      // factored values: the factor of each of the lane's 16 rows
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int i = 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3);
+        osc[r] = (out_scale && i < nr) ? out_scale[r0 + i] : 1.f;
+    }
     if constexpr (!FUSED) {
         if (!wave_has_rows) return;
 #pragma unroll
@@ -39,7 +46,7 @@ __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_h
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int i = 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3);
-                if (i < nr) Y[(size_t)(r0 + i) * F + f] = acc[t][r];
+                if (i < nr) Y[(size_t)(r0 + i) * F + f] = acc[t][r] * osc[r];
             }
         }
     } else {
@@ -50,7 +57,7 @@ __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_h
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int i = 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3);
-                    sOut[i * FT + 32 * t + lo] = acc[t][r];
+                    sOut[i * FT + 32 * t + lo] = acc[t][r] * osc[r];
                 }
         }
         __syncthreads();
@@ -81,7 +88,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, CsrDev R, cons
     const uint4 bits = *reinterpret_cast<const uint4 *>(B.bitmap + ((size_t)slot * kMaxBlock + 32 * w + lo) * 4);
     RemainderRows<FT, VEC> rem;
     if constexpr (FUSED) rem.prepare(R, r0, nr, F, f0, tid);
-    stage_tile<FT, VEC>(H, F, r0, nr, kpad, f0, sH, tid);
+    stage_tile<FT, VEC>(H, F, r0, nr, kpad, f0, sH, tid, B.in_scale);
     __syncthreads();
     if (!FUSED && !has_rows) return;
     const float *tile = WEIGHTED ? B.tiles + (size_t)slot * (kMaxBlock * kMaxBlock) + w * 4096 + l : nullptr;
@@ -107,7 +114,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, CsrDev R, cons
             }
         }
     }
-    write_out<NT, VEC, FUSED>(acc, has_rows, sH, rem, R, H, Y, F, r0, nr, f0, tid);
+    write_out<NT, VEC, FUSED>(acc, has_rows, sH, rem, R, H, Y, F, r0, nr, f0, tid, B.out_scale);
 }
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -132,7 +139,7 @@ constexpr int kKS = kMaxBlock + 8;
 
 template <int FT, int VEC>
 __device__ __forceinline__ void stage_tile_bf16x3(const float *__restrict__ H, int F, int r0, int nr, int f0,
-                                                  uint32_t *sT, int tid)
+                                                  uint32_t *sT, int tid, const float *__restrict__ scale)
 {
     constexpr int UPR = FT / VEC;
     constexpr int ITER = (kMaxBlock / 2 * UPR) / kWG;
@@ -145,6 +152,11 @@ __device__ __forceinline__ void stage_tile_bf16x3(const float *__restrict__ H, i
         for (int q = 0; q < 2; ++q) {
             if (2 * jp + q < nr && ff < F) {
                 load_vec<VEC>(H + (size_t)(r0 + 2 * jp + q) * F + ff, h[it][q]);
+                if (scale) {                            // factored values: the source row's factor, in fp32, before the cut
+                    const float sc = scale[r0 + 2 * jp + q];
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) h[it][q][j] *= sc;
+                }
             } else {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) h[it][q][j] = 0.f;
@@ -186,7 +198,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense_bf16x3(BlocksDev B, CsrDev 
     const uint4 bits = *reinterpret_cast<const uint4 *>(B.bitmap + ((size_t)slot * kMaxBlock + 32 * w + lo) * 4);
     RemainderRows<FT, VEC> rem;
     if constexpr (FUSED) rem.prepare(R, r0, nr, F, f0, tid);
-    stage_tile_bf16x3<FT, VEC>(H, F, r0, nr, f0, sT, tid);
+    stage_tile_bf16x3<FT, VEC>(H, F, r0, nr, f0, sT, tid, B.in_scale);
     __syncthreads();
     if (!FUSED && !has_rows) return;
     floatx16 acc[NT];
@@ -215,7 +227,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense_bf16x3(BlocksDev B, CsrDev 
             }
         }
     }
-    write_out<NT, VEC, FUSED>(acc, has_rows, reinterpret_cast<float *>(sT), rem, R, H, Y, F, r0, nr, f0, tid);
+    write_out<NT, VEC, FUSED>(acc, has_rows, reinterpret_cast<float *>(sT), rem, R, H, Y, F, r0, nr, f0, tid, B.out_scale);
 }
 
 // ---- launchers -----------------------------------------------------------------------------
@@ -267,7 +279,7 @@ int launch_block_dense(const BlocksDev &B, const CsrDev *fused_rem, const float 
     if (B.n_dense <= 0) return AG_OK;
     hipStream_t st = (hipStream_t)stream;
     if (variant == AG_K_BLOCK_DENSE_BF16X3 && B.tiles) {
-        set_error("the bf16x3 dense kernel takes unit-weight blocks only");
+        set_error("the bf16x3 dense kernel takes unit-weight or factored blocks only");
         return AG_ERR_UNSUPPORTED;
     }
     if (fused_rem) return pick_vec<true>(B, *fused_rem, H, Y, F, variant, st);

@@ -26,9 +26,9 @@ COMBOS = {
 DETERMINISTIC = [k for k in COMBOS if not k.endswith("coo")]
 
 
-def usable(name, g):
-    """The bf16x3 dense kernel exists for unit-weight matrices only."""
-    return not (name.endswith("bf16x3") and g.vals is not None)
+def usable(name, g, factored=False):
+    """The bf16x3 dense kernel exists for unit-weight and for factored matrices only."""
+    return not (name.endswith("bf16x3") and g.vals is not None and not factored)
 
 
 def say(*a):
@@ -57,11 +57,13 @@ def check(y_gpu, y_ref, S, what):
 class Case:
     """One graph + features on the GPU, with oracle results computed once."""
 
-    def __init__(self, g, F, seed=0, layout=ag.AG_LAYOUT_ORIGINAL, **opts):
+    def __init__(self, g, F, seed=0, layout=ag.AG_LAYOUT_ORIGINAL, factored=False, **opts):
         import torch
         from ag_inputs import features
         self.torch = torch
-        self.g, self.F, self.layout = g, F, layout
+        self.g, self.F, self.layout, self.factored = g, F, layout, factored
+        if factored:                                     # the generator's own factors of the values
+            opts = dict(opts, row_scale=g.meta.get("row_scale"), col_scale=g.meta.get("col_scale"))
         self.H = features(g.n, F, 100 + seed)
         self.G = features(g.n, F, 200 + seed)
         self.plan = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, F, layout=layout, **opts)
@@ -94,7 +96,7 @@ class Case:
     def check_all_combos(self, combos=None, directions=(0, 1)):
         out = {}
         for name in (combos or COMBOS):
-            if not usable(name, self.g):
+            if not usable(name, self.g, self.factored):
                 continue
             for d in directions:
                 say(f"  combo {name} dir {d} n={self.g.n} F={self.F}")

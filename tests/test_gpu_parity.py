@@ -101,6 +101,44 @@ def test_fused_dense_kernels_with_many_blocks():
             c.close()
 
 
+def test_factored_values_value_free_blocks():
+    """With row_scale / col_scale the diagonal blocks run without stored values (pattern kernels,
+    the bf16 dense form included); results must still match the oracle, which uses the values."""
+    # symmetric GCN normalisation on a graph with dense communities, several widths, ragged blocks
+    gw = gcn_normalise(mixed_density(6, 96, 0.4, 5, 0.05, 29))
+    for F in (32, 64, 128, 24, 7):
+        c = Case(gw, F, block_cap=96, factored=True)
+        st = ag.ag_plan_stats(c.plan)
+        assert st["factored"] == 1 and st["n_dense_blocks"] >= 4
+        c.check_all_combos()
+        c.close()
+    # aggregate-mean: row factors only, non-symmetric matrix, so the backward swaps the roles
+    gm = row_normalise(mixed_density(6, 64, 0.4, 5, 0.05, 31))
+    for F in (32, 20):
+        c = Case(gm, F, block_cap=64, factored=True)
+        assert ag.ag_plan_stats(c.plan)["symmetric"] == 0
+        c.check_all_combos()
+        c.close()
+    # sparse communities (no dense class) and the fused composition at config-3 shape
+    c = Case(config_graph(3, scale=1 / 64), 128, factored=True, layout=ag.AG_LAYOUT_REORDERED)
+    c.check_all_combos()
+    c.close()
+    # many dense-class blocks: the fused dense kernels with scales
+    g0 = mixed_density(272, 40, 0.45, 5, 0.05, 37)
+    c = Case(gcn_normalise(g0), 32, block_cap=40, factored=True)
+    assert ag.ag_plan_stats(c.plan)["n_dense_blocks"] >= ag.AG_MIN_BLOCKS_OWN_LAUNCH
+    c.check_all_combos(combos=["fused_dense", "fused_dense_bf16x3", "fused_narrow", "split_dense_bf16x3"])
+    c.close()
+    # factors that do not reproduce the values are refused
+    bad = gw.meta["row_scale"].copy()
+    bad[5] *= 1.01
+    with pytest.raises(RuntimeError):
+        ag.ag_plan_create(gw.rowptr, gw.colidx, gw.vals, gw.n, 8, row_scale=bad, col_scale=gw.meta["col_scale"],
+                          flags=ag.AG_FLAG_HOST_ONLY)
+    with pytest.raises(RuntimeError):                    # factors need values
+        ag.ag_plan_create(gw.rowptr, gw.colidx, None, gw.n, 8, row_scale=bad, flags=ag.AG_FLAG_HOST_ONLY)
+
+
 def test_power_law_long_rows():
     g = config_graph(2, scale=1 / 16)
     c = Case(g, 128)

@@ -98,6 +98,27 @@ def test_dense_blocks_are_classified():
     assert 0.1 < st["density_intra"] < 0.35
 
 
+def test_factored_values_are_checked_and_leave_the_decomposition_unchanged():
+    from ag_inputs import row_normalise
+    g = gcn_normalise(mixed_density(6, 96, 0.4, 5, 0.05, 29))
+    st = compare_with_oracle(g, block_cap=96, row_scale=g.meta["row_scale"], col_scale=g.meta["col_scale"])
+    assert st["factored"] == 1 and st["unit_weights"] == 0
+    plain = compare_with_oracle(g, block_cap=96)
+    assert plain["factored"] == 0
+    # value-free dense kernels come in at a lower density than the ones that read a value tile
+    assert st["n_dense_blocks"] >= plain["n_dense_blocks"]
+    gm = row_normalise(mixed_density(4, 64, 0.4, 5, 0.05, 31))          # row factors only
+    assert compare_with_oracle(gm, block_cap=64, row_scale=gm.meta["row_scale"])["factored"] == 1
+    bad = g.meta["row_scale"].copy()
+    bad[int(np.argmax(np.diff(g.rowptr)))] *= 1.01                      # a vertex inside a dense community
+    with pytest.raises(RuntimeError):
+        host_plan(g, row_scale=bad, col_scale=g.meta["col_scale"])
+    with pytest.raises(RuntimeError):                                   # factors describe values: vals needed
+        ag.ag_plan_create(g.rowptr, g.colidx, None, g.n, 8, row_scale=bad, flags=ag.AG_FLAG_HOST_ONLY)
+    with pytest.raises(ValueError):
+        host_plan(g, row_scale=bad[:-1])
+
+
 def test_unsorted_rows_are_sorted_and_values_follow():
     g = gcn_normalise(planted_partition(6, 32, 5, 0.7, 8))
     rng = np.random.default_rng(0)
