@@ -53,7 +53,7 @@ __device__ __forceinline__ void chunk_range_lds(int c, float v, int lo, int hi, 
     }
 }
 
-template <int G, int NV, int VEC, bool FUSED>
+template <int G, int NV, int VEC, bool FUSED, bool SCALED>
 __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t *__restrict__ list,
                                                       CsrDev R, const float *__restrict__ H,
                                                       float *__restrict__ Y, int F)
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
     const int myrows = min(rpt, nr - first);
     const int irp = B.i_rowptr[r0 + first + min(gl, myrows)];
     // factored values: lane gl keeps the output factor of the team's row gl (fetched with the row pointers)
-    const float osc = (B.out_scale && gl < myrows) ? B.out_scale[r0 + first + gl] : 1.f;
+    const float osc = (SCALED && B.out_scale && gl < myrows) ? B.out_scale[r0 + first + gl] : 1.f;
     const int ie1 = __shfl(irp, myrows, G);
     int iq = __shfl(irp, 0, G);                         // entry held by lane 0 of ring chunk 0
     int ic0, ic1, ic2;
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
         ld_r(rq + G + gl, rc1, rv1);
         ld_r(rq + 2 * G + gl, rc2, rv2);
     }
-    stage_tile<FT, VEC>(H, F, r0, nr, nr, f0, sH, tid, B.in_scale);
+    stage_tile<FT, VEC>(H, F, r0, nr, nr, f0, sH, tid, SCALED ? B.in_scale : nullptr);
     for (int j = tid; j < FT; j += kWG) sH[kMaxBlock * FT + j] = 0.f;
     __syncthreads();
     for (int i = 0; i < myrows; ++i) {
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
                 k = iq + hi;
             }
         }
-        if (B.out_scale) {                              // factored values: the row's factor on its block sum
+        if (SCALED && B.out_scale) {                    // factored values: the row's factor on its block sum
             const float sc = __shfl(osc, i, G);
 #pragma unroll
             for (int q = 0; q < NV; ++q)
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
     }
 }
 
-template <int G, int NV, int VEC, bool FUSED>
+template <int G, int NV, int VEC, bool FUSED, bool SCALED>
 int launch_one(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev &R, const float *H, float *Y,
                int F, hipStream_t st)
 {
@@ -179,7 +179,7 @@ int launch_one(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev 
         int dev = 0;
         (void)hipGetDevice(&dev);
         if (dev < 0 || dev >= 64 || !prepared[dev].load(std::memory_order_acquire)) {
-            int rc = hip_fail((int)hipFuncSetAttribute((const void *)k_block_sparse<G, NV, VEC, FUSED>,
+            int rc = hip_fail((int)hipFuncSetAttribute((const void *)k_block_sparse<G, NV, VEC, FUSED, SCALED>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
                               "LDS size attribute");
             if (rc) return rc;
@@ -187,7 +187,7 @@ int launch_one(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev 
         }
     }
     dim3 grid(nlist, (F + FT - 1) / FT);
-    hipLaunchKernelGGL((k_block_sparse<G, NV, VEC, FUSED>), grid, dim3(kWG), lds, st, B, list, R, H, Y, F);
+    hipLaunchKernelGGL((k_block_sparse<G, NV, VEC, FUSED, SCALED>), grid, dim3(kWG), lds, st, B, list, R, H, Y, F);
     return hip_fail((int)hipGetLastError(), "block_sparse launch");
 }
 
@@ -195,8 +195,11 @@ template <int G, int NV, int VEC>
 int run(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev *rem, const float *H,
         float *Y, int F, hipStream_t st)
 {
-    if (rem) return launch_one<G, NV, VEC, true>(B, list, nlist, *rem, H, Y, F, st);
-    return launch_one<G, NV, VEC, false>(B, list, nlist, CsrDev(), H, Y, F, st);
+    const bool scaled = B.in_scale || B.out_scale;      // factored values: a separate instantiation keeps the plain path lean
+    if (rem) return scaled ? launch_one<G, NV, VEC, true, true>(B, list, nlist, *rem, H, Y, F, st)
+                           : launch_one<G, NV, VEC, true, false>(B, list, nlist, *rem, H, Y, F, st);
+    return scaled ? launch_one<G, NV, VEC, false, true>(B, list, nlist, CsrDev(), H, Y, F, st)
+                  : launch_one<G, NV, VEC, false, false>(B, list, nlist, CsrDev(), H, Y, F, st);
 }
 
 }  // namespace
