@@ -22,7 +22,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // + (r & 3)][l & 31] of the wave's 32 x 32 tile.  Plain: every lane stores its values (32
 // consecutive features per row and instruction).  FUSED: the tile goes to LDS (the operand tile
 // is no longer needed) and the rows are finished with their remainder entries, one store per row.
-template <int NT, int VEC, bool FUSED>
+template <int NT, int VEC, bool FUSED, bool SCALED>
 __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_has_rows, float *sOut,
                                           RemainderRows<32 * NT, VEC> &rem, const CsrDev &R,
                                           const float *__restrict__ H, float *__restrict__ Y,
@@ -31,11 +31,13 @@ __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_h
 {
     constexpr int FT = 32 * NT;
     const int w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
-    float osc[16];                                      // factored values: the factor of each of the lane's 16 rows
+    float osc[SCALED ? 16 : 1];                         // factored values: the factor of each of the lane's 16 rows
+    if constexpr (SCALED) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int i = 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3);
-        osc[r] = (out_scale && i < nr) ? out_scale[r0 + i] : 1.f;
+        for (int r = 0; r < 16; ++r) {
+            const int i = 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3);
+            osc[r] = (out_scale && i < nr) ? out_scale[r0 + i] : 1.f;
+        }
     }
     if constexpr (!FUSED) {
         if (!wave_has_rows) return;
@@ -46,7 +48,7 @@ __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_h
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int i = 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3);
-                if (i < nr) Y[(size_t)(r0 + i) * F + f] = acc[t][r] * osc[r];
+                if (i < nr) Y[(size_t)(r0 + i) * F + f] = SCALED ? acc[t][r] * osc[SCALED ? r : 0] : acc[t][r];
             }
         }
     } else {
@@ -57,7 +59,7 @@ __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_h
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int i = 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3);
-                    sOut[i * FT + 32 * t + lo] = acc[t][r] * osc[r];
+                    sOut[i * FT + 32 * t + lo] = SCALED ? acc[t][r] * osc[SCALED ? r : 0] : acc[t][r];
                 }
         }
         __syncthreads();
@@ -70,7 +72,7 @@ __device__ __forceinline__ void write_out(const floatx16 (&acc)[NT], bool wave_h
 //   result register r holds D[8 (r / 4) + 4 (l >> 5) + (r & 3)][l & 31].
 // All global loads that do not depend on the staged tile (bit map, remainder row pointers and
 // first topology chunks) are issued before the staging, so they overlap with it.
-template <int NT, int VEC, bool WEIGHTED, bool FUSED>
+template <int NT, int VEC, bool WEIGHTED, bool FUSED, bool SCALED>
 __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, CsrDev R, const float *__restrict__ H,
                                                      float *__restrict__ Y, int F)
 {
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, CsrDev R, cons
     const uint4 bits = *reinterpret_cast<const uint4 *>(B.bitmap + ((size_t)slot * kMaxBlock + 32 * w + lo) * 4);
     RemainderRows<FT, VEC> rem;
     if constexpr (FUSED) rem.prepare(R, r0, nr, F, f0, tid);
-    stage_tile<FT, VEC>(H, F, r0, nr, kpad, f0, sH, tid, B.in_scale);
+    stage_tile<FT, VEC>(H, F, r0, nr, kpad, f0, sH, tid, SCALED ? B.in_scale : nullptr);
     __syncthreads();
     if (!FUSED && !has_rows) return;
     const float *tile = WEIGHTED ? B.tiles + (size_t)slot * (kMaxBlock * kMaxBlock) + w * 4096 + l : nullptr;
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense(BlocksDev B, CsrDev R, cons
             }
         }
     }
-    write_out<NT, VEC, FUSED>(acc, has_rows, sH, rem, R, H, Y, F, r0, nr, f0, tid, B.out_scale);
+    write_out<NT, VEC, FUSED, SCALED>(acc, has_rows, sH, rem, R, H, Y, F, r0, nr, f0, tid, B.out_scale);
 }
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -181,7 +183,7 @@ __device__ __forceinline__ void stage_tile_bf16x3(const float *__restrict__ H, i
 // group): A = A[l & 31][8 (l >> 5) + 0..7], B = B[8 (l >> 5) + 0..7][l & 31], result as above.
 // A is the adjacency block (rows = destinations, 8 consecutive sources = one byte of the row's
 // bit map), B the transposed feature pieces.
-template <int NT, int VEC, bool FUSED>
+template <int NT, int VEC, bool FUSED, bool SCALED>
 __global__ __launch_bounds__(kWG) void k_block_dense_bf16x3(BlocksDev B, CsrDev R, const float *__restrict__ H,
                                                             float *__restrict__ Y, int F)
 {
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense_bf16x3(BlocksDev B, CsrDev 
     const uint4 bits = *reinterpret_cast<const uint4 *>(B.bitmap + ((size_t)slot * kMaxBlock + 32 * w + lo) * 4);
     RemainderRows<FT, VEC> rem;
     if constexpr (FUSED) rem.prepare(R, r0, nr, F, f0, tid);
-    stage_tile_bf16x3<FT, VEC>(H, F, r0, nr, f0, sT, tid, B.in_scale);
+    stage_tile_bf16x3<FT, VEC>(H, F, r0, nr, f0, sT, tid, SCALED ? B.in_scale : nullptr);
     __syncthreads();
     if (!FUSED && !has_rows) return;
     floatx16 acc[NT];
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(kWG) void k_block_dense_bf16x3(BlocksDev B, CsrDev 
             }
         }
     }
-    write_out<NT, VEC, FUSED>(acc, has_rows, reinterpret_cast<float *>(sT), rem, R, H, Y, F, r0, nr, f0, tid, B.out_scale);
+    write_out<NT, VEC, FUSED, SCALED>(acc, has_rows, reinterpret_cast<float *>(sT), rem, R, H, Y, F, r0, nr, f0, tid, B.out_scale);
 }
 
 // ---- launchers -----------------------------------------------------------------------------
@@ -235,7 +237,10 @@ template <int NT, int VEC, bool FUSED>
 int run_bf16x3(const BlocksDev &B, const CsrDev &R, const float *H, float *Y, int F, hipStream_t st)
 {
     dim3 grid(B.n_dense, (F + 32 * NT - 1) / (32 * NT));
-    hipLaunchKernelGGL((k_block_dense_bf16x3<NT, VEC, FUSED>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
+    if (B.in_scale || B.out_scale)                      // factored values: a separate instantiation keeps the plain path lean
+        hipLaunchKernelGGL((k_block_dense_bf16x3<NT, VEC, FUSED, true>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
+    else
+        hipLaunchKernelGGL((k_block_dense_bf16x3<NT, VEC, FUSED, false>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
     return hip_fail((int)hipGetLastError(), "block_dense_bf16x3 launch");
 }
 
@@ -243,10 +248,12 @@ template <int NT, int VEC, bool FUSED>
 int run_f32(const BlocksDev &B, const CsrDev &R, const float *H, float *Y, int F, hipStream_t st)
 {
     dim3 grid(B.n_dense, (F + 32 * NT - 1) / (32 * NT));
-    if (B.tiles)
-        hipLaunchKernelGGL((k_block_dense<NT, VEC, true, FUSED>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
+    if (B.tiles)                                        // weighted and not factored
+        hipLaunchKernelGGL((k_block_dense<NT, VEC, true, FUSED, false>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
+    else if (B.in_scale || B.out_scale)
+        hipLaunchKernelGGL((k_block_dense<NT, VEC, false, FUSED, true>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
     else
-        hipLaunchKernelGGL((k_block_dense<NT, VEC, false, FUSED>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
+        hipLaunchKernelGGL((k_block_dense<NT, VEC, false, FUSED, false>), grid, dim3(kWG), 0, st, B, R, H, Y, F);
     return hip_fail((int)hipGetLastError(), "block_dense launch");
 }
 
