@@ -105,3 +105,25 @@ def test_max_config2_scaled_power_law():
     assert np.array_equal(got["arg"], aref)
     err = np.abs(got["dH"].astype(np.float64) - Dref)
     assert np.all(err <= REL * S + ABS)
+
+
+def test_max_full_size_config3():
+    """The benchmark graph at full size (N = 1,048,576, F = 128): Y bit for bit, argmax exact,
+    adjoint within the aggregation's band.  Among 134 M (row, feature) pairs random fp32 draws do
+    tie now and then, so every feature column is a permutation of N distinct values (multiples of
+    2^-18 around zero, exact in fp32): the argmax is unique everywhere."""
+    g = config_graph(3)
+    say(f"full-size max aggregator: n={g.n} nnz={g.nnz}")
+    rng = np.random.default_rng(11)
+    base = ((np.arange(g.n, dtype=np.float64) - g.n / 2) / 2.0 ** 18).astype(np.float32)
+    H = np.stack([base[rng.permutation(g.n)] for _ in range(128)], axis=1)
+    G = features(g.n, 128, 2)
+    Yref, aref = oracle.spmax(g.rowptr, g.colidx, H)
+    Dref, S = oracle.spmax_t(aref, G)
+    got = run(g, 128, H, G)
+    assert np.array_equal(got["Y"].astype(np.float64), Yref)
+    assert np.array_equal(got["arg"], aref)
+    err = np.abs(got["dH"].astype(np.float64) - Dref)
+    ratio = float((err / (REL * S + ABS)).max())
+    say("adjoint worst err/bound", ratio)
+    assert ratio <= 1.0
