@@ -491,6 +491,83 @@ __global__ __launch_bounds__(kWG) void k_hidden_backward(const float *__restrict
     }
 }
 
+// The same backward step on the fp32 matrix instruction, for hd in {64, 128, 256} and c <= 16, without
+// LDS.  A wavefront owns a slice of 64 hidden columns and walks blocks of 32 rows:
+//   part 1  dPre tile = dQ[32 x 16] . W2T[16 x 64]: the A operand (a row of dQ per lane) comes
+//           straight from global memory, the B operand (the wave's slice of W2T) stays in registers;
+//   the H1 values of the block are loaded once, in the result layout of the instruction (register r
+//           of lane l holds row 8 (r / 4) + 4 (l >> 5) + (r & 3), column l & 31): they mask the dPre
+//           tile, and the very same registers are the A operand of
+//   part 2  dW2 slice += H1^T . dQ, whose k index may run over the block's rows in any order: step s
+//           uses the row that result register s holds, so no data has to move between lanes.
+// With fewer than four column slices the spare wavefronts take the next row blocks.  Every
+// wavefront ends with its own partial of dW2; a second kernel adds them in a fixed order.
+__global__ __launch_bounds__(kWG) void k_hidden_backward_mfma(const float *__restrict__ dQ,
+                                                              const float *__restrict__ W2T,
+                                                              const float *__restrict__ H1, float *__restrict__ dPre,
+                                                              float *__restrict__ part, int64_t N, int c, int hd,
+                                                              int rows_per_wg)
+{
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    // a wavefront owns 32 hidden columns; the work-group's 4 wavefronts cover 128 columns of one
+    // 32-row block (hd = 128: one pass; hd = 256: blockIdx.y picks the half; hd = 64: two row blocks)
+    const int CS = min(hd / 32, 4), RS = 4 / CS;         // column slices per work-group; row sub-blocks per pass
+    const int slice = w % CS, rsub = w / CS;
+    const int col0 = blockIdx.y * 128 + slice * 32;
+    float bw[8];                                         // B operand of part 1: W2T[2 s + hi][col0 + lo]
+#pragma unroll
+    for (int s = 0; s < 8; ++s) bw[s] = (2 * s + hi < c) ? W2T[(size_t)(2 * s + hi) * hd + col0 + lo] : 0.f;
+    floatx16 acc2;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc2[r] = 0.f;
+    const int64_t rb = (int64_t)blockIdx.x * rows_per_wg, re = min(N, rb + rows_per_wg);
+    const bool c16 = (c == 16);
+    for (int64_t R0 = rb + 32 * rsub; R0 < re; R0 += 32 * RS) {
+        // the lane's row of dQ (A operand of part 1), the dQ values in B-operand layout for part 2,
+        // and the H1 values of the block: all loads first
+        float q[16], b2[16], h[16];
+        if (c16 && R0 + lo < re) {
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4) {
+                const float4 v = *reinterpret_cast<const float4 *>(dQ + (R0 + lo) * 16 + 4 * j4);
+                q[4 * j4] = v.x; q[4 * j4 + 1] = v.y; q[4 * j4 + 2] = v.z; q[4 * j4 + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) q[j] = (R0 + lo < re && j < c) ? dQ[(R0 + lo) * c + j] : 0.f;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = R0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+            h[r] = row < re ? H1[row * hd + col0 + lo] : 0.f;
+            b2[r] = (row < re && lo < c) ? dQ[row * c + lo] : 0.f;
+        }
+        floatx16 d;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) d[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) d = __builtin_amdgcn_mfma_f32_32x32x2f32(hi ? q[2 * s + 1] : q[2 * s], bw[s], d, 0, 0, 0);
+        // part 2: step s takes the row held by result register s
+#pragma unroll
+        for (int s = 0; s < 16; ++s) acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(h[s], b2[s], acc2, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = R0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+            if (row < re) dPre[row * hd + col0 + lo] = h[r] > 0.f ? d[r] : 0.f;
+        }
+    }
+    // partial (blockIdx.x, rsub) is filled by the wavefronts (and, for hd = 256, the two work-groups)
+    // that share these rows: each writes its own 32 columns
+    float *o = part + ((size_t)blockIdx.x * RS + rsub) * hd * c;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int m = col0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+        if (lo < c) o[(size_t)m * c + lo] = acc2[r];
+    }
+}
+
+inline bool hidden_backward_on_mfma(int32_t hd, int32_t c) { return (hd == 64 || hd == 128 || hd == 256) && c >= 1 && c <= 16; }
+
 constexpr int kHiddenRowsPerWg = 1024;
 
 template <int EPI>
@@ -578,6 +655,7 @@ size_t hidden_backward_scratch_floats(int64_t N, int32_t hd, int32_t c)
 {
     if (hd < 4 || hd % 4 || hd / 4 > kWG || c > 16) return 0;
     const int64_t wgs = (N + kHiddenRowsPerWg - 1) / kHiddenRowsPerWg;
+    if (hidden_backward_on_mfma(hd, c)) return (size_t)wgs * (hd == 64 ? 2 : 1) * hd * c;
     return (size_t)wgs * hd * c;
 }
 
@@ -585,10 +663,19 @@ int launch_hidden_backward(int64_t N, int32_t hd, int32_t c, const float *dQ, co
                            float *dPre, float *dW2, float *scratch, void *stream)
 {
     if (hd < 4 || hd % 4 || hd / 4 > kWG || c > 16 || c < 1) return AG_ERR_UNSUPPORTED;
-    if ((size_t)(kWG / (hd / 4) - 1) * hd * 16 * sizeof(float) > 65536) return AG_ERR_UNSUPPORTED;   // LDS for the in-group sum
     if (N <= 0) return launch_fill_zero((int64_t)hd * c, dW2, stream);
     hipStream_t st = (hipStream_t)stream;
     const int wgs = (int)((N + kHiddenRowsPerWg - 1) / kHiddenRowsPerWg);
+    if (hidden_backward_on_mfma(hd, c)) {
+        const int parts = wgs * (hd == 64 ? 2 : 1);
+        hipLaunchKernelGGL(k_hidden_backward_mfma, dim3(wgs, hd == 256 ? 2 : 1), dim3(kWG), 0, st, dQ, W2T, H1, dPre, scratch, N, c, hd,
+                           kHiddenRowsPerWg);
+        const int64_t cnt = (int64_t)hd * c;
+        hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((cnt + 31) / 32)), dim3(kWG), 0, st, parts, parts, cnt,
+                           scratch, dW2);
+        return hip_fail((int)hipGetLastError(), "hidden_backward launch");
+    }
+    if ((size_t)(kWG / (hd / 4) - 1) * hd * 16 * sizeof(float) > 65536) return AG_ERR_UNSUPPORTED;   // LDS for the in-group sum
     const int groups = kWG / (hd / 4);
     const size_t lds = (size_t)(groups - 1) * hd * 16 * sizeof(float);
     hipLaunchKernelGGL((k_hidden_backward<16>), dim3(wgs), dim3(kWG), lds, st, dQ, W2T, H1, dPre, scratch, N, c, hd,
