@@ -174,6 +174,78 @@ __global__ __launch_bounds__(kWG) void k_gemm_tn(const float *__restrict__ A, co
         }
 }
 
+// The same product without LDS: the fp32 matrix instruction takes A[k + (l >> 5)][m0 + (l & 31)] and
+// B[k + (l >> 5)][n0 + (l & 31)] as operands of lane l, which are plain coalesced 4-byte loads of
+// the two row-major inputs, so every wave streams its own operands from global memory (the
+// neighbouring wave's copy comes from L1) with KU k-steps of loads in flight and no barrier.
+template <int WM, int WN, int KU>
+__global__ __launch_bounds__(kWG) void k_gemm_tn_direct(const float *__restrict__ A, const float *__restrict__ B,
+                                                        float *__restrict__ part, int64_t K, int m, int n,
+                                                        int64_t rows_per_chunk, float *__restrict__ colsum_part)
+{
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    const int wm = w >> 1, wn = w & 1;
+    const int m0 = blockIdx.y * (2 * WM * 32) + wm * WM * 32, n0 = blockIdx.z * (2 * WN * 32) + wn * WN * 32;
+    const int64_t k_begin = (int64_t)blockIdx.x * rows_per_chunk, k_end = min(K, k_begin + rows_per_chunk);
+    bool am[WM], bn[WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) am[i] = m0 + 32 * i + lo < m;
+#pragma unroll
+    for (int j = 0; j < WN; ++j) bn[j] = n0 + 32 * j + lo < n;
+    floatx16 acc[WM][WN];
+    float cs[WN];
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+        cs[j] = 0.f;
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    }
+    for (int64_t k0 = k_begin; k0 < k_end; k0 += 2 * KU) {
+        float a[KU][WM], b[KU][WN];
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            const int64_t row = k0 + 2 * u + hi;
+            const bool ok = row < k_end;
+#pragma unroll
+            for (int i = 0; i < WM; ++i) a[u][i] = (ok && am[i]) ? A[row * m + m0 + 32 * i + lo] : 0.f;
+#pragma unroll
+            for (int j = 0; j < WN; ++j) b[u][j] = (ok && bn[j]) ? B[row * n + n0 + 32 * j + lo] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+#pragma unroll
+            for (int j = 0; j < WN; ++j) cs[j] += b[u][j];
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][i], b[u][j], acc[i][j], 0, 0, 0);
+        }
+    }
+    if (colsum_part != nullptr && blockIdx.y == 0 && wm == 0) {
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const float t = cs[j] + __shfl_xor(cs[j], 32);
+            if (hi == 0 && bn[j]) colsum_part[(size_t)blockIdx.x * n + n0 + 32 * j + lo] = t;
+        }
+    }
+    float *out = part + (size_t)blockIdx.x * m * n;
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            if (!bn[j]) continue;
+            const int col = n0 + 32 * j + lo;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + 32 * i + 8 * (r >> 2) + 4 * hi + (r & 3);
+                if (row < m) out[(size_t)row * n + col] = acc[i][j][r];
+            }
+        }
+}
+
 __global__ __launch_bounds__(kWG) void k_sum_partials(int nchunks, int per_group, int64_t count,
                                                       const float *__restrict__ part, float *__restrict__ C)
 {
@@ -624,8 +696,10 @@ int launch_gemm_tn(int64_t K, int32_t m, int32_t n, const float *A, const float 
         dim3 grid(nchunks, (m + 63) / 64, 1);
         hipLaunchKernelGGL((k_gemm_tn<2, 2, 1, 1, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     } else if (n > 32) {
+        // wide outputs: operands straight from global memory, no LDS (0.69 ms against 0.76 ms for the
+        // LDS-staged tile on the 1 M x 128 x 256 weight gradient; 8 k-steps of loads in flight beat 4 and 16)
         dim3 grid(nchunks, (m + 127) / 128, (n + 255) / 256);
-        hipLaunchKernelGGL((k_gemm_tn<2, 2, 2, 4, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
+        hipLaunchKernelGGL((k_gemm_tn_direct<2, 4, 8>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
     } else {
         dim3 grid(nchunks, (m + 255) / 256, 1);
         hipLaunchKernelGGL((k_gemm_tn<4, 1, 2, 1, kKSdef>), grid, dim3(kWG), 0, st, A, B, scratch, K, m, n, rows_per_chunk, cs_part);
