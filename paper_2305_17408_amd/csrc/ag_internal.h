@@ -3,6 +3,8 @@
 #include <cstdint>
 #include <memory>
 #include <string>
+#include <algorithm>
+#include <thread>
 #include <vector>
 
 #include "adaptgear.h"
@@ -35,6 +37,20 @@ struct ReorderResult {
     std::vector<int32_t> perm, iperm, blk_ptr, comm;
     int32_t n_blocks = 0;
 };
+
+// run fn(t, begin, end) over [0,n) on a few host threads (t = thread index); returns the thread count
+template <class Fn>
+int parallel_ranges(int64_t n, Fn fn, int64_t min_per_thread = 4096)
+{
+    unsigned hw = std::thread::hardware_concurrency();
+    int nt = (int)std::min<int64_t>(std::max(1u, std::min(hw, 16u)), std::max<int64_t>(1, n / min_per_thread));
+    if (nt <= 1) { fn(0, (int64_t)0, n); return 1; }
+    std::vector<std::thread> th;
+    for (int t = 0; t < nt; ++t)
+        th.emplace_back([=] { fn(t, n * t / nt, n * (t + 1) / nt); });
+    for (auto &x : th) x.join();
+    return nt;
+}
 
 // reorder.cpp
 void build_pattern_graph(const HostCsr &A, const HostCsr &At, WGraph &g);

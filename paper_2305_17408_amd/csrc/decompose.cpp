@@ -10,23 +10,6 @@
 
 namespace ag {
 
-namespace {
-
-// run fn(t, begin, end) over [0,n) on a few host threads
-template <class Fn>
-void parallel_ranges(int64_t n, Fn fn)
-{
-    unsigned hw = std::thread::hardware_concurrency();
-    int nt = (int)std::min<int64_t>(std::max(1u, std::min(hw, 16u)), std::max<int64_t>(1, n / 4096));
-    if (nt <= 1) { fn(0, (int64_t)0, n); return; }
-    std::vector<std::thread> th;
-    for (int t = 0; t < nt; ++t)
-        th.emplace_back([=] { fn(t, n * t / nt, n * (t + 1) / nt); });
-    for (auto &x : th) x.join();
-}
-
-}  // namespace
-
 int ingest_csr(const ag_csr *in, HostCsr &out, std::string &err)
 {
     if (!in || in->n < 0 || in->nnz < 0 || (in->n + 1 > 0 && !in->rowptr) || (in->nnz > 0 && !in->colidx)) {
@@ -90,15 +73,35 @@ void transpose_csr(const HostCsr &A, HostCsr &At)
     At.rowptr.assign(n + 1, 0);
     At.col.resize(nnz);
     At.val.resize(A.val.empty() ? 0 : nnz);
-    for (int64_t e = 0; e < nnz; ++e) At.rowptr[A.col[e] + 1]++;
-    for (int64_t i = 0; i < n; ++i) At.rowptr[i + 1] += At.rowptr[i];
-    std::vector<int32_t> at(At.rowptr.begin(), At.rowptr.end() - 1);
-    for (int64_t i = 0; i < n; ++i)                 // ascending i keeps every row of A^T sorted
-        for (int32_t e = A.rowptr[i]; e < A.rowptr[i + 1]; ++e) {
-            const int32_t p = at[A.col[e]]++;
-            At.col[p] = (int32_t)i;
-            if (!A.val.empty()) At.val[p] = A.val[e];
+    // Row ranges of A go to threads; every thread counts its entries per column, the counts become
+    // write positions ordered by (column, thread), and every thread scatters its rows in ascending
+    // order: each row of A^T comes out sorted by source row, whatever the thread count.
+    std::vector<std::vector<int32_t>> cnt(16);
+    std::vector<int64_t> lo_of(16, 0), hi_of(16, 0);
+    const int nt = parallel_ranges(n, [&](int t, int64_t lo, int64_t hi) {
+        lo_of[t] = lo; hi_of[t] = hi;
+        cnt[t].assign(n, 0);
+        for (int32_t e = A.rowptr[lo]; e < A.rowptr[hi]; ++e) cnt[t][A.col[e]]++;
+    }, 65536);
+    int32_t run = 0;
+    for (int64_t c = 0; c < n; ++c) {
+        At.rowptr[c] = run;
+        for (int t = 0; t < nt; ++t) {
+            const int32_t k = cnt[t][c];
+            cnt[t][c] = run;                          // becomes thread t's write position in column c
+            run += k;
         }
+    }
+    At.rowptr[n] = run;
+    parallel_ranges(n, [&](int t, int64_t lo, int64_t hi) {
+        std::vector<int32_t> &at = cnt[t];
+        for (int64_t i = lo; i < hi; ++i)
+            for (int32_t e = A.rowptr[i]; e < A.rowptr[i + 1]; ++e) {
+                const int32_t p = at[A.col[e]]++;
+                At.col[p] = (int32_t)i;
+                if (!A.val.empty()) At.val[p] = A.val[e];
+            }
+    }, 65536);
 }
 
 bool bitwise_equal(const HostCsr &A, const HostCsr &B)

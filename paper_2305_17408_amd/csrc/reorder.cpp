@@ -19,11 +19,11 @@ void build_pattern_graph(const HostCsr &A, const HostCsr &At, WGraph &g)
     const int64_t n = A.n;
     g.n = (int32_t)n;
     g.xadj.assign(n + 1, 0);
-    g.adj.clear();
-    g.adj.reserve((size_t)A.nnz());
-    for (int64_t v = 0; v < n; ++v) {
+    // merge of the two sorted rows without the diagonal; emit == nullptr only counts
+    auto merge_row = [&](int64_t v, int32_t *emit) -> int64_t {
         int32_t a = A.rowptr[v], ae = A.rowptr[v + 1];
         int32_t b = At.rowptr[v], be = At.rowptr[v + 1];
+        int64_t cnt = 0;
         while (a < ae || b < be) {
             int32_t x;
             if (b >= be || (a < ae && A.col[a] <= At.col[b])) {
@@ -33,10 +33,21 @@ void build_pattern_graph(const HostCsr &A, const HostCsr &At, WGraph &g)
             } else {
                 x = At.col[b++];
             }
-            if (x != v) g.adj.push_back(x);
+            if (x != v) {
+                if (emit) emit[cnt] = x;
+                ++cnt;
+            }
         }
-        g.xadj[v + 1] = (int64_t)g.adj.size();
-    }
+        return cnt;
+    };
+    parallel_ranges(n, [&](int, int64_t lo, int64_t hi) {
+        for (int64_t v = lo; v < hi; ++v) g.xadj[v + 1] = merge_row(v, nullptr);
+    });
+    for (int64_t v = 0; v < n; ++v) g.xadj[v + 1] += g.xadj[v];
+    g.adj.resize((size_t)g.xadj[n]);
+    parallel_ranges(n, [&](int, int64_t lo, int64_t hi) {
+        for (int64_t v = lo; v < hi; ++v) merge_row(v, g.adj.data() + g.xadj[v]);
+    });
     g.ew.assign(g.adj.size(), 1);
     g.nw.assign((size_t)n, 1);
 }
@@ -105,7 +116,9 @@ int32_t propagate(const WGraph &g, int32_t level, int32_t cap, int32_t sweeps,
     return k;
 }
 
-// Clusters become nodes; node weights add, parallel edges add, inner edges vanish.
+// Clusters become nodes; node weights add, parallel edges add, inner edges vanish.  The neighbours
+// of a cluster are listed in order of first appearance while its members are walked in ascending
+// order, so the result does not depend on how the clusters are shared out among the threads.
 void contract(const WGraph &g, const std::vector<int32_t> &cluster, int32_t k, WGraph &c)
 {
     const int32_t n = g.n;
@@ -120,28 +133,43 @@ void contract(const WGraph &g, const std::vector<int32_t> &cluster, int32_t k, W
     c.n = k;
     c.nw.assign(k, 0);
     c.xadj.assign(k + 1, 0);
-    c.adj.clear();
-    c.ew.clear();
-    std::vector<int64_t> wsum(k, 0);
-    std::vector<int32_t> seen;
-    for (int32_t q = 0; q < k; ++q) {
-        seen.clear();
-        for (int32_t m = start[q]; m < start[q + 1]; ++m) {
-            const int32_t v = member[m];
-            c.nw[q] += g.nw[v];
-            for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) {
-                const int32_t t = cluster[g.adj[e]];
-                if (t == q) continue;
-                if (wsum[t] == 0) seen.push_back(t);
-                wsum[t] += g.ew[e];
+    struct Piece { int64_t lo = 0, hi = 0; std::vector<int32_t> adj, ew; };
+    std::vector<Piece> piece(16);
+    const int nt = parallel_ranges(k, [&](int t, int64_t lo, int64_t hi) {
+        Piece &P = piece[t];
+        P.lo = lo; P.hi = hi;
+        std::vector<int64_t> wsum(k, 0);
+        std::vector<int32_t> seen;
+        for (int64_t q = lo; q < hi; ++q) {
+            seen.clear();
+            int32_t w = 0;
+            for (int32_t mi = start[q]; mi < start[q + 1]; ++mi) {
+                const int32_t v = member[mi];
+                w += g.nw[v];
+                for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) {
+                    const int32_t t2 = cluster[g.adj[e]];
+                    if (t2 == q) continue;
+                    if (wsum[t2] == 0) seen.push_back(t2);
+                    wsum[t2] += g.ew[e];
+                }
             }
+            c.nw[q] = w;
+            for (int32_t t2 : seen) {
+                P.adj.push_back(t2);
+                P.ew.push_back((int32_t)wsum[t2]);
+                wsum[t2] = 0;
+            }
+            c.xadj[q + 1] = (int64_t)seen.size();
         }
-        for (int32_t t : seen) {
-            c.adj.push_back(t);
-            c.ew.push_back((int32_t)wsum[t]);
-            wsum[t] = 0;
-        }
-        c.xadj[q + 1] = (int64_t)c.adj.size();
+    }, n >= 65536 ? 64 : (int64_t)1 << 40);              // a cluster stands for many vertices; small graphs stay on one thread
+    for (int32_t q = 0; q < k; ++q) c.xadj[q + 1] += c.xadj[q];
+    c.adj.resize((size_t)c.xadj[k]);
+    c.ew.resize((size_t)c.xadj[k]);
+    for (int t = 0; t < nt; ++t) {
+        const Piece &P = piece[t];
+        if (P.adj.empty()) continue;
+        std::copy(P.adj.begin(), P.adj.end(), c.adj.begin() + c.xadj[P.lo]);
+        std::copy(P.ew.begin(), P.ew.end(), c.ew.begin() + c.xadj[P.lo]);
     }
 }
 
