@@ -66,10 +66,18 @@ int32_t propagate(const WGraph &g, int32_t level, int32_t cap, int32_t sweeps,
     for (int32_t v = 0; v < n; ++v)
         for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) tot[v] += g.ew[e];
     std::vector<int32_t> touched;
+    // A node is evaluated only if its outcome can differ from "stay": `dirty` = it or a neighbour
+    // moved since its last evaluation (its connection weights or its own label changed), `sens` =
+    // its last evaluation depended on label sizes (a stronger neighbouring label was full, or it
+    // was weakly attached).  Otherwise the same weights and the same current label give the same
+    // "stay", whatever happened to the sizes: skipping it changes nothing in the result.
+    std::vector<uint8_t> dirty(n, 1), sens(n, 0);
     for (int32_t s = 0; s < sweeps; ++s) {
         int64_t moved = 0;
+        const bool all = (level == 0 && s == 1);        // the joining threshold just changed for everyone
         for (int32_t v = 0; v < n; ++v) {
             if (tot[v] == 0) continue;
+            if (!all && !dirty[v] && !sens[v]) continue;
             touched.clear();
             for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) {
                 const int32_t L = label[g.adj[e]];
@@ -82,10 +90,15 @@ int32_t propagate(const WGraph &g, int32_t level, int32_t cap, int32_t sweeps,
             // strongest admissible neighbouring label; equal strength -> smallest id
             int32_t cand = -1;
             int64_t cand_conn = 0;
+            bool blocked = false;                       // a label that would win is full
             for (int32_t L : touched) {
                 const int64_t c = conn[L];
                 conn[L] = 0;
-                if (L == cur || c < need || size[L] + w > cap) continue;
+                if (L == cur || c < need) continue;
+                if (size[L] + w > cap) {
+                    if (c > own || own < need) blocked = true;
+                    continue;
+                }
                 if (c > cand_conn || (c == cand_conn && L < cand)) { cand_conn = c; cand = L; }
             }
             int32_t target = cur;
@@ -96,11 +109,15 @@ int32_t propagate(const WGraph &g, int32_t level, int32_t cap, int32_t sweeps,
             } else if (size[cur] > w && size[v] == 0) {
                 target = v;                                             // ... or back to its own empty label
             }
+            dirty[v] = 0;
+            sens[v] = blocked || own < need;
             if (target != cur) {
                 size[cur] -= w;
                 size[target] += w;
                 label[v] = target;
                 ++moved;
+                dirty[v] = 1;
+                for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) dirty[g.adj[e]] = 1;
             }
         }
         if (!moved) break;
