@@ -175,8 +175,9 @@ int ag_plan_selector_info(const ag_plan *p, int32_t dir, ag_selector_info *out);
  * around its subgraph kernels.  ag_plan_profile waits for the recorded events and returns the
  * sums since profiling was switched on.  With AG_COMPOSE_SPLIT class_ms[0..2] are the dense-
  * class block kernel, the sparse-class block kernel and the remainder kernels; with
- * AG_COMPOSE_FUSED class_ms[0] is the fused block kernel and class_ms[2] the tail/long-row
- * kernels; with AG_COMPOSE_FULL_CSR everything is in class_ms[2]. */
+ * AG_COMPOSE_FUSED class_ms[0] is the fused block kernel (all blocks, or the dense class when it
+ * runs its own kernel, then class_ms[1] is the fused kernel of the sparse class) and class_ms[2]
+ * the tail/long-row kernels; with the one-CSR compositions everything is in class_ms[2]. */
 typedef struct {
     int64_t calls;
     double  class_ms[3];
