@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libadaptgear.
 #pragma once
 #include <cstdint>
+#include <exception>
 #include <memory>
 #include <string>
 #include <algorithm>
@@ -38,7 +39,8 @@ struct ReorderResult {
     int32_t n_blocks = 0;
 };
 
-// run fn(t, begin, end) over [0,n) on a few host threads (t = thread index); returns the thread count
+// run fn(t, begin, end) over [0,n) on a few host threads (t = thread index); returns the thread
+// count.  An exception thrown by fn on a worker (an allocation failure, say) is re-thrown on the caller.
 template <class Fn>
 int parallel_ranges(int64_t n, Fn fn, int64_t min_per_thread = 4096)
 {
@@ -46,9 +48,13 @@ int parallel_ranges(int64_t n, Fn fn, int64_t min_per_thread = 4096)
     int nt = (int)std::min<int64_t>(std::max(1u, std::min(hw, 16u)), std::max<int64_t>(1, n / min_per_thread));
     if (nt <= 1) { fn(0, (int64_t)0, n); return 1; }
     std::vector<std::thread> th;
+    std::vector<std::exception_ptr> err(nt);
     for (int t = 0; t < nt; ++t)
-        th.emplace_back([=] { fn(t, n * t / nt, n * (t + 1) / nt); });
+        th.emplace_back([=, &err] {
+            try { fn(t, n * t / nt, n * (t + 1) / nt); } catch (...) { err[t] = std::current_exception(); }
+        });
     for (auto &x : th) x.join();
+    for (auto &e : err) if (e) std::rethrow_exception(e);
     return nt;
 }
 
