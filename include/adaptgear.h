@@ -74,7 +74,7 @@ typedef struct {
     int32_t max_levels;     /* coarsening levels (12)                                          */
     int32_t order_levels;   /* extra levels that only order the communities so that connected   *
                              * ones are adjacent (3; negative = plain ascending-id order)         */
-    int32_t trials;         /* timed runs per candidate in the selector (3)                    */
+    int32_t trials;         /* timed runs per candidate in the selector (3; at most 15)        */
     int32_t layout;         /* AG_LAYOUT_*                                                     */
     int32_t flags;          /* AG_FLAG_*                                                       */
     float   dense_density;  /* blocks at least this dense may use the dense kernels (0.20;      *

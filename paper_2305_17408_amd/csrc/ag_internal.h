@@ -49,11 +49,19 @@ int parallel_ranges(int64_t n, Fn fn, int64_t min_per_thread = 4096)
     if (nt <= 1) { fn(0, (int64_t)0, n); return 1; }
     std::vector<std::thread> th;
     std::vector<std::exception_ptr> err(nt);
-    for (int t = 0; t < nt; ++t)
-        th.emplace_back([=, &err] {
-            try { fn(t, n * t / nt, n * (t + 1) / nt); } catch (...) { err[t] = std::current_exception(); }
-        });
+    th.reserve(nt);
+    std::exception_ptr spawn_err;
+    for (int t = 0; t < nt; ++t) {
+        try {
+            th.emplace_back([=, &err] {
+                try { fn(t, n * t / nt, n * (t + 1) / nt); } catch (...) { err[t] = std::current_exception(); }
+            });
+        } catch (...) {                                  // no more threads: finish this range here
+            try { fn(t, n * t / nt, n * (t + 1) / nt); } catch (...) { spawn_err = std::current_exception(); }
+        }
+    }
     for (auto &x : th) x.join();
+    if (spawn_err) std::rethrow_exception(spawn_err);
     for (auto &e : err) if (e) std::rethrow_exception(e);
     return nt;
 }
@@ -169,6 +177,11 @@ size_t hidden_backward_scratch_floats(int64_t N, int32_t hd, int32_t c);
 int launch_hidden_backward(int64_t N, int32_t hd, int32_t c, const float *dQ, const float *W2T, const float *H1,
                            float *dPre, float *dW2, float *scratch, void *stream);
 int launch_transpose_small(int32_t rows, int32_t cols, const float *in, float *out, void *stream);
+
+// api.cpp
+// ag_aggregate with the settled kernel choice and `partial` (partial_bytes of device memory) in
+// place of the plan's own long-row scratch; allocates nothing, refuses calls that need a trial.
+int aggregate_settled(ag_plan *p, const float *X, float *Y, float *partial, size_t partial_bytes, void *stream);
 
 void set_error(const std::string &msg);
 int  hip_fail(int hip_error_code, const char *what);

@@ -8,15 +8,19 @@
 #include <cstring>
 
 #include "ag_internal.h"
+#include "selector.h"
 
 namespace ag {
 
 static thread_local std::string g_err;
-void set_error(const std::string &msg) { g_err = msg; }
+void set_error(const std::string &msg)
+{
+    try { g_err = msg; } catch (...) { }                 // out of memory: the code still reaches the caller
+}
 int hip_fail(int code, const char *what)
 {
     if (code == (int)hipSuccess) return AG_OK;
-    g_err = std::string(what) + ": " + hipGetErrorString((hipError_t)code);
+    try { g_err = std::string(what) + ": " + hipGetErrorString((hipError_t)code); } catch (...) { }
     return AG_ERR_HIP;
 }
 
@@ -137,33 +141,6 @@ struct Topology {
     }
 };
 
-// Feedback-driven kernel selection for one direction (Sec. 3.3): during the first calls every
-// candidate runs 1 warm-up + `trials` timed times with events around each subgraph kernel;
-// afterwards the fastest candidate per subgraph class is kept.  A second round compares the
-// ways of composing the pieces by their total time.
-struct Selector {
-    int forced[AG_NUM_CLS];
-    int choice[AG_NUM_CLS];
-    int ncand[AG_NUM_CLS];
-    int phase = 0;          // 0: per-class trials, 1: composition trials, 2: frozen
-    int cand = 0, rep = 0, calls = 0;
-    std::vector<float> samples[AG_NUM_CLS][4];
-    float median_ms[AG_NUM_CLS][4];
-    float best_ms[AG_NUM_CLS];      // fastest finished candidate so far (early abandon of hopeless ones)
-    float total_trial_ms = 0.f;
-
-    void reset(bool keep_forced)
-    {
-        for (int c = 0; c < AG_NUM_CLS; ++c) {
-            if (!keep_forced) forced[c] = -1;
-            choice[c] = 0;
-            best_ms[c] = -1.f;
-            for (int k = 0; k < 4; ++k) { samples[c][k].clear(); median_ms[c][k] = -1.f; }
-        }
-        phase = 0; cand = 0; rep = 0; total_trial_ms = 0.f;
-    }
-};
-
 }  // namespace ag
 
 using namespace ag;
@@ -194,13 +171,6 @@ struct ag_plan {
 };
 
 namespace {
-
-static float median_of(std::vector<float> v)
-{
-    if (v.empty()) return -1.f;
-    std::sort(v.begin(), v.end());
-    return v[v.size() / 2];
-}
 
 void init_selector(ag_plan *p, int dir, bool keep_forced)
 {
@@ -234,7 +204,7 @@ int plan_device_buffers(ag_plan *p)
 
 // Enqueue one aggregation with a fixed kernel choice.  `ev` (4 events) may be null.
 int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, hipStream_t st,
-               hipEvent_t *ev)
+               hipEvent_t *ev, float *partial)
 {
     const Topology &t = *p->topo;
     const DevDir &D = t.d[dir_idx];
@@ -250,7 +220,7 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
         if ((rc = launch_csr_rows(D.full, H, Y, F, 0, n, 0,
                                   k[AG_CLS_COMPOSE] == AG_COMPOSE_FULL_CSR_WIDE ? AG_K_CSR_WIDE : AG_K_CSR_NARROW, st)))
             return rc;
-        if ((rc = launch_csr_long(D.full, H, Y, F, p->partial, 0, st))) return rc;
+        if ((rc = launch_csr_long(D.full, H, Y, F, partial, 0, st))) return rc;
         break;
     case AG_COMPOSE_FUSED:
         if (k[AG_CLS_BLOCKS_DENSE] != AG_K_BLOCK_SPARSE && D.blk.n_dense >= AG_MIN_BLOCKS_OWN_LAUNCH) {
@@ -264,7 +234,7 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
             if (ev) { (void)hipEventRecord(ev[1], st); (void)hipEventRecord(ev[2], st); }
         }
         if ((rc = launch_csr_rows(D.inter, H, Y, F, nbr, n, 0, wide, st))) return rc;
-        if ((rc = launch_csr_long(D.inter, H, Y, F, p->partial, nbr, st))) return rc;
+        if ((rc = launch_csr_long(D.inter, H, Y, F, partial, nbr, st))) return rc;
         break;
     default:
         if (k[AG_CLS_BLOCKS_DENSE] != AG_K_BLOCK_SPARSE)
@@ -279,7 +249,7 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
             if ((rc = launch_coo(D.inter, H, Y, F, nbr, st))) return rc;
         } else {
             if ((rc = launch_csr_rows(D.inter, H, Y, F, 0, n, nbr, wide, st))) return rc;
-            if ((rc = launch_csr_long(D.inter, H, Y, F, p->partial, nbr, st))) return rc;
+            if ((rc = launch_csr_long(D.inter, H, Y, F, partial, nbr, st))) return rc;
         }
         break;
     }
@@ -287,62 +257,7 @@ int run_choice(ag_plan *p, int dir_idx, const int *k, const float *H, float *Y, 
     return AG_OK;
 }
 
-int fastest(Selector &s, int c)
-{
-    int best = -1;
-    for (int k = 0; k < s.ncand[c]; ++k) {
-        s.median_ms[c][k] = median_of(s.samples[c][k]);
-        if (s.median_ms[c][k] >= 0 && (best < 0 || s.median_ms[c][k] < s.median_ms[c][best])) best = k;
-    }
-    return best < 0 ? 0 : best;                        // ties and "nothing measured" -> lowest id
-}
-
-void finish_phase0(Selector &s)
-{
-    for (int c = 0; c < AG_CLS_COMPOSE; ++c) s.choice[c] = s.forced[c] >= 0 ? s.forced[c] : fastest(s, c);
-}
-
-void finish_phase1(Selector &s)
-{
-    const int c = AG_CLS_COMPOSE;
-    s.choice[c] = s.forced[c] >= 0 ? s.forced[c] : fastest(s, c);
-}
-
-// Decide what this call runs; returns true when the call is a timed trial.
-bool next_choice(ag_plan *p, Selector &s, int *k)
-{
-    for (;;) {
-        if (s.phase == 0) {
-            int maxc = 1;
-            bool any_free = false;
-            for (int c = 0; c < AG_CLS_COMPOSE; ++c)
-                if (s.forced[c] < 0 && s.ncand[c] > 1) { maxc = std::max(maxc, s.ncand[c]); any_free = true; }
-            if (!any_free || s.cand >= maxc) {
-                finish_phase0(s);
-                s.phase = 1; s.cand = 0; s.rep = 0;
-                continue;
-            }
-            for (int c = 0; c < AG_CLS_COMPOSE; ++c)
-                k[c] = s.forced[c] >= 0 ? s.forced[c] : std::min(s.cand, s.ncand[c] - 1);
-            k[AG_CLS_COMPOSE] = AG_COMPOSE_SPLIT;        // without blocks this is the remainder kernel alone
-            return true;
-        }
-        if (s.phase == 1) {
-            const int c = AG_CLS_COMPOSE;
-            if (s.forced[c] >= 0 || s.cand >= s.ncand[c]) {
-                finish_phase1(s);
-                s.phase = 2;
-                continue;
-            }
-            for (int q = 0; q < AG_CLS_COMPOSE; ++q) k[q] = s.choice[q];
-            k[c] = s.cand;
-            return true;
-        }
-        for (int q = 0; q < AG_NUM_CLS; ++q) k[q] = s.choice[q];
-        return false;
-    }
-}
-
+// Read the events of a trial call and hand the four intervals to the selector.
 void record_trial(ag_plan *p, Selector &s, const int *k, hipEvent_t *ev)
 {
     float ms[4] = {0, 0, 0, 0};
@@ -351,44 +266,7 @@ void record_trial(ag_plan *p, Selector &s, const int *k, hipEvent_t *ev)
     (void)hipEventElapsedTime(&ms[1], ev[1], ev[2]);
     (void)hipEventElapsedTime(&ms[2], ev[2], ev[3]);
     (void)hipEventElapsedTime(&ms[3], ev[0], ev[3]);
-    s.total_trial_ms += ms[3];
-    const bool timed = s.rep > 0;                       // rep 0 is the warm-up
-    // A candidate whose warm-up run is already 4x slower than the best finished one is hopeless:
-    // its warm-up time is kept as its only sample and the timed repetitions are skipped.
-    bool hopeless = false;
-    if (!timed) {
-        if (s.phase == 0) {
-            bool any = false, all_slow = true;
-            for (int c = 0; c < AG_CLS_COMPOSE; ++c)
-                if (s.forced[c] < 0 && s.cand < s.ncand[c] && s.ncand[c] > 1) {
-                    any = true;
-                    if (!(s.best_ms[c] > 0 && ms[c] > 4.f * s.best_ms[c])) all_slow = false;
-                }
-            hopeless = any && all_slow;
-        } else {
-            const float b = s.best_ms[AG_CLS_COMPOSE];
-            hopeless = b > 0 && ms[3] > 4.f * b;
-        }
-    }
-    if (timed || hopeless) {
-        if (s.phase == 0) {
-            for (int c = 0; c < AG_CLS_COMPOSE; ++c)
-                if (s.forced[c] < 0 && s.cand < s.ncand[c]) s.samples[c][k[c]].push_back(ms[c]);
-        } else {
-            s.samples[AG_CLS_COMPOSE][k[AG_CLS_COMPOSE]].push_back(ms[3]);
-        }
-    }
-    if (++s.rep > p->trials || hopeless) {
-        // candidate finished: remember the fastest median per class
-        for (int c = 0; c < AG_NUM_CLS; ++c) {
-            if ((s.phase == 0) == (c == AG_CLS_COMPOSE)) continue;
-            if (s.forced[c] >= 0 || s.cand >= s.ncand[c]) continue;
-            const float m = median_of(s.samples[c][k[c]]);
-            if (m > 0 && (s.best_ms[c] < 0 || m < s.best_ms[c])) s.best_ms[c] = m;
-        }
-        s.rep = 0;
-        ++s.cand;
-    }
+    selector_record(s, p->trials, k, ms);
 }
 
 constexpr int kProfRing = 64;
@@ -413,10 +291,10 @@ void prof_drain(ag_plan *p)
     p->prof_next = 0;
 }
 
-int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
+int check_call(const ag_plan *p, const float *X, const float *Y)
 {
     if (!p) { set_error("null plan"); return AG_ERR_INVALID; }
-    Topology &t = *p->topo;
+    const Topology &t = *p->topo;
     if (t.host_only) { set_error("plan was created with AG_FLAG_HOST_ONLY"); return AG_ERR_UNSUPPORTED; }
     if (t.n == 0) return AG_OK;
     if (!X || !Y) { set_error("null argument"); return AG_ERR_INVALID; }
@@ -425,6 +303,14 @@ int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
         set_error("feature matrices must be 16-byte aligned");
         return AG_ERR_INVALID;
     }
+    return AG_OK;
+}
+
+int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
+{
+    int rc0 = check_call(p, X, Y);
+    if (rc0 || p->topo->n == 0) return rc0;
+    Topology &t = *p->topo;
     hipStream_t st = (hipStream_t)stream;
     const int dir_idx = (dir == AG_DIR_BWD && !t.symmetric) ? 1 : 0;
     Selector &s = p->sel[dir];
@@ -438,7 +324,7 @@ int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
     }
     int k[AG_NUM_CLS];
     ++s.calls;
-    const bool trial = next_choice(p, s, k);
+    const bool trial = selector_next(s, k);
     if (trial && !p->ev[0])
         for (auto &e : p->ev)
             if ((rc = hip_fail((int)hipEventCreate(&e), "event create"))) return rc;
@@ -448,7 +334,7 @@ int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
         evs = p->prof_ev.data() + 4 * p->prof_next;
         p->prof_pending.push_back({dir, p->prof_next++});
     }
-    if ((rc = run_choice(p, dir_idx, k, in, out, st, evs))) return rc;
+    if ((rc = run_choice(p, dir_idx, k, in, out, st, evs, p->partial))) return rc;
     if (trial) record_trial(p, s, k, p->ev);
     if (p->layout == AG_LAYOUT_ORIGINAL)
         if ((rc = launch_permute_rows(t.perm_dev, t.n, p->F, p->tmp_out, Y, true, st))) return rc;
@@ -456,6 +342,55 @@ int aggregate_dir(ag_plan *p, int dir, const float *X, float *Y, void *stream)
 }
 
 }  // namespace
+
+namespace ag {
+
+// Forward aggregation with the plan's settled kernel choice and caller-supplied memory for the
+// partial sums of long rows.  Creates no event, grows no container and allocates no device or
+// host memory: a call that would need a selector trial is refused instead.
+int aggregate_settled(ag_plan *p, const float *X, float *Y, float *partial, size_t partial_bytes, void *stream)
+{
+    int rc = check_call(p, X, Y);
+    if (rc || p->topo->n == 0) return rc;
+    const Topology &t = *p->topo;
+    Selector &s = p->sel[AG_DIR_FWD];
+    int k[AG_NUM_CLS];
+    bool all_forced = true;
+    for (int c = 0; c < AG_NUM_CLS; ++c) all_forced = all_forced && s.forced[c] >= 0;
+    if (all_forced) {
+        for (int c = 0; c < AG_NUM_CLS; ++c) k[c] = s.forced[c];
+    } else if (s.phase == 2) {
+        for (int c = 0; c < AG_NUM_CLS; ++c) k[c] = s.choice[c];
+    } else {
+        set_error("the kernel choice is not settled yet: run ag_aggregate until the selector has frozen, "
+                  "or pin all four classes with ag_plan_force_kernels");
+        return AG_ERR_UNSUPPORTED;
+    }
+    const size_t need = (size_t)t.max_segments * (size_t)p->F * sizeof(float);
+    if (need > partial_bytes) {
+        try {
+            set_error("long-row partial sums need " + std::to_string(need) + " bytes of scratch, more than the " +
+                      std::to_string(partial_bytes) + " bytes of the static buffer");
+        } catch (...) { }
+        return AG_ERR_UNSUPPORTED;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const float *in = X;
+    float *out = Y;
+    if (p->layout == AG_LAYOUT_ORIGINAL) {               // staging buffers exist since plan creation
+        if ((rc = launch_permute_rows(t.perm_dev, t.n, p->F, X, p->tmp_in, false, st))) return rc;
+        in = p->tmp_in;
+        out = p->tmp_out;
+    }
+    if ((rc = run_choice(p, 0, k, in, out, st, nullptr, partial))) return rc;
+    if (p->layout == AG_LAYOUT_ORIGINAL)
+        if ((rc = launch_permute_rows(t.perm_dev, t.n, p->F, p->tmp_out, Y, true, st))) return rc;
+    return AG_OK;
+}
+
+}  // namespace ag
+
+using namespace ag;
 
 extern "C" {
 
@@ -479,7 +414,7 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
     if (o.order_levels == 0) o.order_levels = 3;          // negative = keep the communities in id order
     if (o.trials == 0) o.trials = 3;
     if (o.block_cap < 1 || o.block_cap > kMaxBlock || o.min_block < 1 || o.sweeps < 1 || o.max_levels < 1 ||
-        o.trials < 1 || (o.layout != AG_LAYOUT_ORIGINAL && o.layout != AG_LAYOUT_REORDERED) ||
+        o.trials < 1 || o.trials > kMaxTrials || (o.layout != AG_LAYOUT_ORIGINAL && o.layout != AG_LAYOUT_REORDERED) ||
         (!o.dev_alloc) != (!o.dev_free)) {
         set_error("option out of range");
         return AG_ERR_INVALID;
@@ -592,14 +527,20 @@ int ag_plan_clone_for_width(const ag_plan *p, int32_t F2, ag_plan **out)
     *out = nullptr;
     auto *q = new (std::nothrow) ag_plan();
     if (!q) { set_error("host allocation failed"); return AG_ERR_NOMEM; }
-    q->topo = p->topo;
-    q->F = F2;
-    q->layout = p->layout;
-    q->trials = p->trials;
-    init_selector(q, 0, false);
-    init_selector(q, 1, false);
-    int rc = plan_device_buffers(q);
-    if (rc) { delete q; return rc; }
+    try {
+        q->topo = p->topo;
+        q->F = F2;
+        q->layout = p->layout;
+        q->trials = p->trials;
+        init_selector(q, 0, false);
+        init_selector(q, 1, false);
+        int rc = plan_device_buffers(q);
+        if (rc) { delete q; return rc; }
+    } catch (const std::bad_alloc &) {
+        delete q;
+        set_error("host allocation failed");
+        return AG_ERR_NOMEM;
+    }
     *out = q;
     return AG_OK;
 }
@@ -673,7 +614,14 @@ int ag_plan_set_profiling(ag_plan *p, int32_t on)
         for (int c = 0; c < 3; ++c) p->prof_ms[d][c] = 0;
     }
     if (on && p->prof_ev.empty()) {
-        p->prof_ev.assign(4 * kProfRing, nullptr);
+        try {
+            p->prof_pending.reserve(kProfRing);           // later calls push without allocating
+            p->prof_ev.assign(4 * kProfRing, nullptr);
+        } catch (const std::bad_alloc &) {
+            p->prof_ev.clear();
+            set_error("host allocation failed");
+            return AG_ERR_NOMEM;
+        }
         for (auto &e : p->prof_ev) {
             int rc = hip_fail((int)hipEventCreate(&e), "event create");
             if (rc) return rc;
