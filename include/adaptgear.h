@@ -115,6 +115,21 @@ int ag_aggregate(ag_plan *p, const float *H_dev, float *Y_dev, void *hip_stream)
 /* dH = A^T.G, the backward of ag_aggregate (training, Sec. 5 "Benchmarks"). */
 int ag_aggregate_t(ag_plan *p, const float *G_dev, float *dH_dev, void *hip_stream);
 
+/* ag_aggregate for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels and the same result, but the scratch
+ * memory of the long-row kernels (partial sums of row segments) is a static device array of
+ * AG_STATIC_SCRATCH_BYTES per GPU instead of plan-owned memory, and the call allocates nothing on
+ * the host or the device and creates no events.
+ *   - the kernel choice must be settled: the forward selector has frozen (ag_plan_selector_info),
+ *     or all four classes are pinned with ag_plan_force_kernels; otherwise AG_ERR_UNSUPPORTED
+ *     (a selector trial would need events);
+ *   - the plan's long-row segments times F floats must fit the static array; otherwise
+ *     AG_ERR_UNSUPPORTED with the sizes in ag_last_error();
+ *   - all calls on one GPU share that GPU's array (whatever the plan): calls that overlap in time
+ *     on one GPU race, also across streams and plans.  Nothing in it has to start at zero. */
+#define AG_STATIC_SCRATCH_BYTES (32u << 20)
+int ag_aggregate_static(ag_plan *p, const float *H_dev, float *Y_dev, void *hip_stream);
+
 /* dst[new] = src[perm[new]] (inverse == 0: caller order -> plan order) or
  * dst[perm[new]] = src[new] (inverse != 0).  N x F device matrices, no aliasing. */
 int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int32_t F,

@@ -27,6 +27,7 @@ AG_MIN_BLOCKS_OWN_LAUNCH = 256
 AG_K_CSR_NARROW, AG_K_CSR_WIDE, AG_K_COO = 0, 1, 2
 AG_COMPOSE_SPLIT, AG_COMPOSE_FUSED, AG_COMPOSE_FULL_CSR, AG_COMPOSE_FULL_CSR_WIDE = 0, 1, 2, 3
 AG_DIR_FWD, AG_DIR_BWD = 0, 1
+AG_STATIC_SCRATCH_BYTES = 32 << 20
 
 _i32p = C.POINTER(C.c_int32)
 _f32p = C.POINTER(C.c_float)
@@ -99,7 +100,7 @@ class ag_gcn_io(C.Structure):
 EXPORTS = ["ag_plan_create", "ag_plan_clone_for_width", "ag_plan_destroy", "ag_aggregate",
            "ag_aggregate_t", "ag_permute_rows", "ag_plan_force_kernels", "ag_plan_selector_info",
            "ag_plan_export", "ag_plan_stats", "ag_plan_set_profiling", "ag_plan_profile", "ag_last_error", "ag_gin_layer", "ag_gin_layer_t",
-           "ag_gcn_workspace_bytes", "ag_gcn_step", "ag_gin_workspace_bytes", "ag_gin_step", "ag_aggregate_max", "ag_aggregate_max_t"]
+           "ag_gcn_workspace_bytes", "ag_gcn_step", "ag_gin_workspace_bytes", "ag_gin_step", "ag_aggregate_max", "ag_aggregate_max_t", "ag_aggregate_static"]
 
 _lib = None
 
@@ -123,6 +124,7 @@ def lib() -> C.CDLL:
         L.ag_plan_destroy.restype = None
         L.ag_aggregate.argtypes = [vp, vp, vp, vp]
         L.ag_aggregate_t.argtypes = [vp, vp, vp, vp]
+        L.ag_aggregate_static.argtypes = [vp, vp, vp, vp]
         L.ag_permute_rows.argtypes = [vp, vp, vp, C.c_int32, C.c_int32, vp]
         L.ag_plan_force_kernels.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32]
         L.ag_plan_selector_info.argtypes = [vp, C.c_int32, C.POINTER(ag_selector_info)]
@@ -219,6 +221,10 @@ def ag_plan_destroy(plan) -> None:
 
 def ag_aggregate(plan, H, Y, stream=None) -> None:
     _check(lib().ag_aggregate(plan, _ptr(H), _ptr(Y), _stream(stream)))
+
+
+def ag_aggregate_static(plan, H, Y, stream=None) -> None:
+    _check(lib().ag_aggregate_static(plan, _ptr(H), _ptr(Y), _stream(stream)))
 
 
 def ag_aggregate_t(plan, G, dH, stream=None) -> None:

@@ -13,7 +13,7 @@ OUT = os.path.join(HERE, "libadaptgear.so")
 BUILD = os.path.join(HERE, "_build")
 
 SOURCES = ["api.cpp", "gcn.cpp", "gin.cpp", "reorder.cpp", "decompose.cpp",
-           "kernels_csr.hip", "kernels_block.hip", "kernels_dense.hip", "kernels_misc.hip", "kernels_gemm.hip", "kernels_gemm_b3.hip", "kernels_coo.hip", "kernels_max.hip"]
+           "kernels_csr.hip", "kernels_block.hip", "kernels_dense.hip", "kernels_misc.hip", "kernels_gemm.hip", "kernels_gemm_b3.hip", "kernels_coo.hip", "kernels_max.hip", "noalloc.hip"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wno-unused-result"]
