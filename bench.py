@@ -69,16 +69,19 @@ def algorithmic_bytes(st, F, compose, cls, dense_kernel=0):
     return total
 
 
-def measured_traffic(config, F, compose):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summaries, or None."""
+def measured_traffic(config, F, choice):
+    """(HBM bytes per launch of the dominant kernel, where the figure comes from) from the committed
+    rocprofv3 --pmc summaries, for exactly this workload, width and kernel choice [dense-class kernel,
+    sparse-class kernel, remainder kernel, composition]; (None, reason) when no committed counter run
+    covers that choice: the figure is measured in separate profiler runs, not in this run."""
     try:
         for line in open(os.path.join(ROOT, "profiles", "hbm_traffic_bytes.txt")):
             t = line.split()
-            if len(t) == 4 and not line.startswith("#") and (int(t[0]), int(t[1]), int(t[2])) == (config, F, compose):
-                return int(t[3])
-    except OSError:
+            if len(t) >= 8 and not line.startswith("#") and [int(x) for x in t[:6]] == [config, F] + list(choice):
+                return int(t[6]), f"profiles/{t[8] if len(t) > 8 else 'hbm_traffic_bytes.txt'}, rocprofv3 --pmc runs of {t[7]}"
+    except (OSError, ValueError):
         pass
-    return None
+    return None, "no committed counter run for this workload, width and kernel choice"
 
 
 def brief(index, steps):
@@ -126,6 +129,130 @@ def brief(index, steps):
             "n_blocks": st["n_blocks"], "n_dense_blocks": st["n_dense_blocks"], "n_long_rows": st["n_long_rows"],
             "density_full": st["density_full"], "density_intra": st["density_intra"],
             "density_inter": st["density_inter"], "plan_device_bytes": st["device_bytes"]}
+
+
+def captured_intra(g, st):
+    """Share of the graph's edges that the reordering keeps inside diagonal blocks, next to the share
+    the generator planted inside its communities (self-loops left out on both sides)."""
+    edges = g.meta.get("edges")
+    if not edges:
+        return {}
+    got = (st["nnz_intra"] - st["n_block_rows"]) / 2.0 / edges
+    planted = g.meta.get("planted_intra_frac", 0.0)
+    return {"intra_edge_frac_captured": round(got, 4), "intra_edge_frac_planted": round(planted, 4),
+            "captured_over_planted": round(got / planted, 4) if planted > 0 else None}
+
+
+def event_medians(fn, calls):
+    """Median and spread (ms) of `calls` individually timed launches of fn() with events on the
+    current stream (the stream the binding launches on)."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(calls)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in ev)
+    return t[len(t) // 2], t[0], t[-1]
+
+
+def pin(ag, plan, compose, dense, rem):
+    for d in (0, 1):
+        ag.ag_plan_force_kernels(plan, ag.AG_CLS_COMPOSE, d, compose)
+        ag.ag_plan_force_kernels(plan, ag.AG_CLS_BLOCKS_DENSE, d, dense)
+        ag.ag_plan_force_kernels(plan, ag.AG_CLS_BLOCKS_SPARSE, d, 0)
+        ag.ag_plan_force_kernels(plan, ag.AG_CLS_REMAINDER, d, rem)
+
+
+def unpin(ag, plan):
+    for d in (0, 1):
+        for c in range(4):
+            ag.ag_plan_force_kernels(plan, c, d, -1)
+
+
+def adaptive_vs_single_format(index, calls):
+    """The breakdown of the paper's Sec. 6.2 on the mixed-density workload, ms per step (forward +
+    backward, median of `calls` steps timed with events):
+      single format (one kernel over the whole reordered matrix, O1 of the paper):
+        one_csr_narrow / one_csr_wide   the CSR kernel with one / several lane groups per row
+      static subgraph-level kernel sets (no selector; O2 of the paper is the first one):
+        csr_intra+coo_inter             block-sparse kernel for every block, COO kernel for the remainder
+        csr_intra+csr_inter             block-sparse kernel for every block, CSR remainder, best composition
+        dense_f32+csr_inter             fp32 MFMA kernel for every block of >= 32 rows (plan with
+                                        dense_density ~ 0), CSR remainder, best composition
+        dense_bf16x3+csr_inter          the same on the bf16 MFMA form (unit-weight matrices)
+      adaptive (O3)                     what the selector froze on
+    The adaptive set can at best equal the fastest static set (it is one of them, found by timing);
+    the target is its ratio to the best single-format kernel."""
+    import torch
+    import paper_2305_17408_amd as ag
+    from ag_inputs import config_graph, CONFIGS, features
+    cfg = CONFIGS[index]
+    F = cfg["F"]
+    g = config_graph(index)
+    H = torch.from_numpy(features(g.n, F, 7)).cuda()
+    G = torch.from_numpy(features(g.n, F, 8)).cuda()
+    Y, dH = torch.empty_like(H), torch.empty_like(H)
+    plan = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, F, layout=ag.AG_LAYOUT_REORDERED)
+    st = ag.ag_plan_stats(plan)
+
+    def step(p):
+        ag.ag_aggregate(p, H, Y)
+        ag.ag_aggregate_t(p, G, dH)
+
+    def timed(p, k=calls):
+        for _ in range(3):
+            step(p)
+        return event_medians(lambda: step(p), k)[0]
+
+    n = 0
+    while n < 200 and not (ag.ag_plan_selector_info(plan, 0)["frozen"] and ag.ag_plan_selector_info(plan, 1)["frozen"]):
+        step(plan)
+        n += 1
+    choice = ag.ag_plan_selector_info(plan, 0)["choice"]
+    adaptive = timed(plan)
+    single, static = {}, {}
+    for name, (c, r) in {"one_csr_narrow": (2, 0), "one_csr_wide": (3, 1)}.items():
+        pin(ag, plan, c, 0, r)
+        single[name] = timed(plan)
+    pin(ag, plan, 0, 0, 2)
+    static["csr_intra+coo_inter"] = timed(plan, 10)
+    best = None
+    for c in (0, 1):
+        pin(ag, plan, c, 0, 0)
+        t = timed(plan)
+        best = t if best is None else min(best, t)
+    static["csr_intra+csr_inter"] = best
+    ag.ag_plan_destroy(plan)
+    plan = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, F, layout=ag.AG_LAYOUT_REORDERED, dense_density=1e-9)
+    st2 = ag.ag_plan_stats(plan)
+    kinds = {"dense_f32+csr_inter": 1}
+    if g.vals is None:
+        kinds["dense_bf16x3+csr_inter"] = 2
+    for name, k in kinds.items():
+        best = None
+        for c in (0, 1):
+            pin(ag, plan, c, k, 0)
+            t = timed(plan)
+            best = t if best is None else min(best, t)
+        static[name] = best
+    ag.ag_plan_destroy(plan)
+    best_single = min(single, key=single.get)
+    best_static = min(static, key=static.get)
+    out = {"workload": f"configs[{index}] {cfg['name']}: N={g.n}, nnz={g.nnz}, F={F}, forward + backward",
+           "calls": calls, "unit": "ms per step (median)",
+           "adaptive_ms": round(adaptive, 5), "adaptive_choice_fwd": choice,
+           "single_format_ms": {k: round(v, 5) for k, v in single.items()},
+           "static_sets_ms": {k: round(v, 5) for k, v in static.items()},
+           "best_single_format": best_single,
+           "speedup_over_best_single_format": round(single[best_single] / adaptive, 3),
+           "best_static_set": best_static,
+           "adaptive_over_best_static_set": round(adaptive / static[best_static], 3),
+           "blocks": st["n_blocks"], "dense_class_blocks": st["n_dense_blocks"],
+           "dense_class_blocks_in_all_dense_plan": st2["n_dense_blocks"]}
+    log(f"[bench] adaptive vs single format: {out}")
+    return out
 
 
 def density_sweep():
@@ -184,8 +311,14 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="index of the benchmark workload (0-based, see ag_inputs.CONFIGS)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN training-step timing")
+    ap.add_argument("--no-mixed", action="store_true",
+                    help="skip the adaptive-versus-single-format comparison on the mixed-density workload (configs[4])")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time the other four workloads (short runs) and add them under 'other_workloads'")
+    ap.add_argument("--pin", default="",
+                    help="pin the kernels instead of letting the selector choose: COMPOSE[,DENSE[,REMAINDER]] with "
+                         "COMPOSE in split|fused|full|full_wide, DENSE in 0|1|2 (block-sparse, fp32 MFMA, bf16x3 MFMA), "
+                         "REMAINDER in 0|1|2 (CSR narrow, CSR wide, COO); for profiling one kernel set in isolation")
     ap.add_argument("--density-sweep", action="store_true",
                     help="instead of the benchmark, time every kernel candidate over a sweep of subgraph densities")
     args = ap.parse_args()
@@ -225,6 +358,10 @@ def main():
     ag.ag_permute_rows(plan, G, Gp, F, False)
     Y, dH = torch.empty_like(H), torch.empty_like(H)
     torch.cuda.synchronize()
+    if args.pin:
+        t = args.pin.split(",")
+        pin(ag, plan, {"split": 0, "fused": 1, "full": 2, "full_wide": 3}[t[0]], int(t[1]) if len(t) > 1 else 0,
+            int(t[2]) if len(t) > 2 else 0)
 
     def step():
         ag.ag_aggregate(plan, Hp, Y)
@@ -256,6 +393,14 @@ def main():
     gflops = flop / (ms_step * 1e-3) / 1e9
     compulsory = 2 * (4 * (g.n + 1) + (4 + (0 if g.vals is None else 4)) * g.nnz + 8 * g.n * F)
     log(f"[bench] {ms_step:.4f} ms/step  {gflops:.1f} GFLOP/s  effective {compulsory / ms_step / 1e6:.1f} GB/s")
+    # forward, backward and whole steps timed one by one with events: medians of >= 50 calls
+    ncall = max(50, args.steps)
+    med = {"calls": ncall}
+    for name, fn in (("forward", lambda: ag.ag_aggregate(plan, Hp, Y)),
+                     ("backward", lambda: ag.ag_aggregate_t(plan, Gp, dH)), ("step", step)):
+        m, lo, hi = event_medians(fn, ncall)
+        med[name] = {"median_ms": round(m, 5), "min_ms": round(lo, 5), "max_ms": round(hi, 5)}
+    log(f"[bench] medians over {ncall} calls: {med}")
 
     # the same steps again with HIP events around every subgraph kernel (roofline figures)
     ag.ag_plan_set_profiling(plan, True)
@@ -291,9 +436,12 @@ def main():
         dom_name = "k_block_sparse" + ("<..., FUSED=true>" if compose == 1 else "")
     abytes = algorithmic_bytes(st, F, compose, dom, sel[0]["choice"][0])
     achieved = abytes / (per_class[dom] * 1e-3) / 1e9 if per_class[dom] > 0 else 0.0
+    traffic, traffic_source = measured_traffic(args.config, F, sel[0]["choice"])
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(args.config, F, compose),
+                "traffic": traffic, "traffic_source": traffic_source,
+                # the whole forward aggregation against the bytes no algorithm can avoid (every array once)
+                "frac_compulsory": round(compulsory / 2 / (med["forward"]["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "kernel": dom_name, "class": cls_names[dom], "avg_launch_ms": round(per_class[dom], 5),
                 "algorithmic_bytes_per_launch": int(abytes),
                 "per_class_ms": {cls_names[c]: round(per_class[c], 5) for c in per_class}}
@@ -315,13 +463,15 @@ def main():
         "config": {"workload": f"configs[{args.config}] {cfg['name']}: N={g.n}, nnz={g.nnz}, F={F}, "
                                "one forward + one backward aggregation, plan-ordered features",
                    "n": g.n, "nnz": g.nnz, "F": F, "layout": "reordered"},
+        "medians": med,
         "effective_hbm_gbs": round(compulsory / ms_step / 1e6, 1),
         "compulsory_bytes_per_step": int(compulsory),
         "plan_create_s": round(t_plan, 2), "selector_steps": sel_calls, "selector_s": round(t_sel, 3),
         "selector_choice": {"fwd": sel[0]["choice"], "bwd": sel[1]["choice"]},
-        "plan": {k: st[k] for k in ("n_blocks", "n_block_rows", "n_dense_blocks", "nnz_intra", "nnz_inter",
-                                    "n_long_rows", "sec_reorder", "sec_split", "sec_build", "sec_upload",
-                                    "device_bytes")},
+        "plan": {**{k: st[k] for k in ("n_blocks", "n_block_rows", "n_dense_blocks", "nnz_intra", "nnz_inter",
+                                       "n_long_rows", "n_long_segments", "sec_reorder", "sec_split", "sec_build",
+                                       "sec_upload", "device_bytes")},
+                 **captured_intra(g, st)},
         "roofline": roofline,
         "remainder_path": remainder,
         "selector_trial_ms": {"compositions_fwd": compose_ms,
@@ -441,6 +591,10 @@ def main():
                                "single_thread_value": round(flop / single / 1e9, 3)}
         log(f"[bench] cpu oracle: {multi:.2f}s with {oracle.num_threads()} threads, {single:.2f}s single-threaded")
     ag.ag_plan_destroy(plan)
+    del H, G, Hp, Gp, Y, dH
+    torch.cuda.empty_cache()
+    if not args.no_mixed:
+        out["adaptive_vs_single_format"] = adaptive_vs_single_format(4, max(50, args.steps))
     if args.all_configs:
         out["other_workloads"] = [brief(i, max(50, args.steps)) for i in range(len(CONFIGS)) if i != args.config]
     print(json.dumps(out), flush=True)

@@ -38,6 +38,7 @@ def _load():
         _lib = ctypes.CDLL(_LIB_PATH)
         _lib.orc_num_threads.restype = ctypes.c_int
         _lib.orc_reorder.restype = ctypes.c_int
+        _lib.orc_reorder_method.restype = ctypes.c_int
         _lib.orc_split.restype = ctypes.c_int
     return _lib
 
@@ -125,8 +126,9 @@ def spmax_t(arg, G):
     return D, S
 
 
-def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels=12, order_levels=3):
-    """Community reordering (paper Sec. 2.2 / 4.2); see orc_reorder in ag_oracle.c."""
+def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels=12, order_levels=3, method=0):
+    """Community reordering (paper Sec. 2.2 / 4.2); see orc_reorder_method in ag_oracle.c.
+    method 0 = multilevel label propagation, 1 = agglomeration by integer modularity gain."""
     lib = _load()
     rowptr, colidx = _i32(rowptr), _i32(colidx)
     n = rowptr.size - 1
@@ -135,8 +137,8 @@ def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels
     blk = np.empty(n + 1, np.int32)
     comm = np.empty(n, np.int32)
     nb = ctypes.c_int32(0)
-    rc = lib.orc_reorder(ctypes.c_int64(n), _p(rowptr, ctypes.c_int32), _p(colidx, ctypes.c_int32),
-                         ctypes.c_int32(block_cap), ctypes.c_int32(min_block), ctypes.c_int32(sweeps),
+    rc = lib.orc_reorder_method(ctypes.c_int64(n), _p(rowptr, ctypes.c_int32), _p(colidx, ctypes.c_int32),
+                         ctypes.c_int32(method), ctypes.c_int32(block_cap), ctypes.c_int32(min_block), ctypes.c_int32(sweeps),
                          ctypes.c_int32(max_levels), ctypes.c_int32(order_levels),
                          _p(perm, ctypes.c_int32), _p(iperm, ctypes.c_int32),
                          _p(blk, ctypes.c_int32), ctypes.byref(nb), _p(comm, ctypes.c_int32))

@@ -27,6 +27,10 @@
  *                   reading used here is a multilevel, size-constrained label
  *                   propagation in pure integer arithmetic (spelled out at the
  *                   function).
+ *   orc_reorder_method  the same with a choice of the community detection:
+ *                   0 = the label propagation above, 1 = one pass of size-constrained
+ *                   agglomeration by the integer modularity gain (spelled out at
+ *                   agglomerate_by_gain); ordering levels and layout are shared.
  *   orc_split       decomposition into intra- / inter-community subgraphs
  *                   (Sec. 3.3 first paragraphs, Sec. 4.2 second stage).
  *
@@ -346,6 +350,94 @@ static int contract(const wgraph *g, const i32 *cluster, i32 k, wgraph *c)
 }
 
 /*
+ * Second community-detection method (Sec. 4.2 leaves the choice of the partitioner to the user and
+ * Sec. 6.1 compares two of them): one pass of size-constrained agglomeration by the integer
+ * modularity gain, in the spirit of incremental-aggregation orderings.
+ *   Every vertex starts as a community of its own with degree deg = number of its neighbours;
+ *   M2 = sum of all degrees (twice the edge count).  Vertices are visited once, in ascending
+ *   degree (ties: ascending id); isolated vertices are skipped.  The visited vertex u stands for
+ *   the community it is the root of (itself plus everything merged into it so far).  For every
+ *   other community r that one of u's members touches, with conn = number of edges between the
+ *   two, the gain of merging is  conn * M2 - deg[u] * deg[r]  (the modularity difference times a
+ *   positive constant, so integers suffice).  Among the communities with a positive gain and
+ *   size[u] + size[r] <= cap the largest gain wins (ties: smallest root id) and u's community is
+ *   merged into it: sizes and degrees add up, r stays the root.  Without such a community u's
+ *   community stays as it is (it can still receive others later).
+ * Cluster ids are dense, numbered by first appearance when scanning the vertices in ascending id.
+ */
+typedef struct { i64 deg; i32 v; } degkey_t;
+static int cmp_degkey(const void *a, const void *b)
+{
+    const degkey_t *x = (const degkey_t *)a, *y = (const degkey_t *)b;
+    if (x->deg != y->deg) return (x->deg > y->deg) - (x->deg < y->deg);
+    return (x->v > y->v) - (x->v < y->v);
+}
+
+static i32 agglomerate_by_gain(const wgraph *g, i32 cap, i32 *cluster)
+{
+    const i32 n = g->n;
+    const size_t nn = (size_t)(n ? n : 1);
+    i32 *root = (i32 *)malloc(sizeof(i32) * nn);      /* community (root vertex) of every vertex */
+    i32 *next = (i32 *)malloc(sizeof(i32) * nn);      /* member lists: singly linked, head = root */
+    i32 *last = (i32 *)malloc(sizeof(i32) * nn);
+    i32 *size = (i32 *)malloc(sizeof(i32) * nn);
+    i64 *deg = (i64 *)malloc(sizeof(i64) * nn);
+    i64 *conn = (i64 *)calloc(nn, sizeof(i64));
+    i32 *cand = (i32 *)malloc(sizeof(i32) * nn);
+    degkey_t *order = (degkey_t *)malloc(sizeof(degkey_t) * nn);
+    i64 M2 = 0;
+    for (i32 v = 0; v < n; ++v) {
+        root[v] = v; next[v] = -1; last[v] = v; size[v] = g->nw[v];
+        deg[v] = 0;
+        for (i64 e = g->xadj[v]; e < g->xadj[v + 1]; ++e) deg[v] += g->ew[e];
+        M2 += deg[v];
+        order[v].deg = deg[v];
+        order[v].v = v;
+    }
+    qsort(order, (size_t)n, sizeof(degkey_t), cmp_degkey);
+    for (i32 t = 0; t < n; ++t) {
+        const i32 u = order[t].v;
+        if (order[t].deg == 0) continue;
+        i32 nc = 0;
+        for (i32 x = u; x >= 0; x = next[x])
+            for (i64 e = g->xadj[x]; e < g->xadj[x + 1]; ++e) {
+                const i32 r = root[g->adj[e]];
+                if (r == u) continue;
+                if (conn[r] == 0) cand[nc++] = r;
+                conn[r] += g->ew[e];
+            }
+        i32 best = -1;
+        i64 best_gain = 0;
+        for (i32 c = 0; c < nc; ++c) {
+            const i32 r = cand[c];
+            const i64 gain = conn[r] * M2 - deg[u] * deg[r];
+            if (gain > 0 && size[u] + size[r] <= cap &&
+                (gain > best_gain || (gain == best_gain && r < best))) {
+                best = r;
+                best_gain = gain;
+            }
+        }
+        for (i32 c = 0; c < nc; ++c) conn[cand[c]] = 0;
+        if (best >= 0) {
+            for (i32 x = u; x >= 0; x = next[x]) root[x] = best;
+            next[last[best]] = u;
+            last[best] = last[u];
+            size[best] += size[u];
+            deg[best] += deg[u];
+        }
+    }
+    i32 *newid = size;                        /* reuse */
+    for (i32 v = 0; v < n; ++v) newid[v] = -1;
+    i32 k = 0;
+    for (i32 v = 0; v < n; ++v) {
+        if (newid[root[v]] < 0) newid[root[v]] = k++;
+        cluster[v] = newid[root[v]];
+    }
+    free(root); free(next); free(last); free(size); free(deg); free(conn); free(cand); free(order);
+    return k;
+}
+
+/*
  * Community reordering.
  *   levels: run propagate_level, map every original vertex to its cluster,
  *   contract, and repeat on the coarse graph while a level still shrinks the
@@ -366,8 +458,8 @@ static int cmp_ordkey(const void *a, const void *b)
     return (x->c > y->c) - (x->c < y->c);
 }
 
-int orc_reorder(i64 n, const i32 *rowptr, const i32 *col, i32 cap, i32 min_block, i32 sweeps,
-                i32 max_levels, i32 order_levels, i32 *perm, i32 *iperm, i32 *blk_ptr, i32 *nb_out, i32 *comm)
+int orc_reorder_method(i64 n, const i32 *rowptr, const i32 *col, i32 method, i32 cap, i32 min_block, i32 sweeps,
+                       i32 max_levels, i32 order_levels, i32 *perm, i32 *iperm, i32 *blk_ptr, i32 *nb_out, i32 *comm)
 {
     wgraph g;
     memset(&g, 0, sizeof(g));
@@ -375,6 +467,10 @@ int orc_reorder(i64 n, const i32 *rowptr, const i32 *col, i32 cap, i32 min_block
     for (i64 v = 0; v < n; ++v) comm[v] = (i32)v;
     i32 ncomm = (i32)n;
     i32 level = 0;
+    if (method == 1 && g.n > 0) {              /* agglomeration by modularity gain: one pass, one level */
+        ncomm = agglomerate_by_gain(&g, cap, comm);
+        wgraph_free(&g);
+    }
     while (g.n > 0) {
         i32 *cluster = (i32 *)malloc(sizeof(i32) * (size_t)g.n);
         i32 k = propagate_level(&g, level, cap, sweeps, cluster);
@@ -458,6 +554,14 @@ int orc_reorder(i64 n, const i32 *rowptr, const i32 *col, i32 cap, i32 min_block
     *nb_out = nb;
     free(csize); free(cstart); free(ord);
     return 0;
+}
+
+/* method 0: multilevel size-constrained label propagation (the default) */
+int orc_reorder(i64 n, const i32 *rowptr, const i32 *col, i32 cap, i32 min_block, i32 sweeps,
+                i32 max_levels, i32 order_levels, i32 *perm, i32 *iperm, i32 *blk_ptr, i32 *nb_out, i32 *comm)
+{
+    return orc_reorder_method(n, rowptr, col, 0, cap, min_block, sweeps, max_levels, order_levels, perm, iperm,
+                              blk_ptr, nb_out, comm);
 }
 
 /* ------------------------------------------------------------------------ */

@@ -59,7 +59,9 @@ __global__ __launch_bounds__(kWG) void k_csr_segments(CsrDev A, const float *__r
 {
     constexpr int W = 64;
     const int tid = threadIdx.x;
-    const int seg = blockIdx.x * (kWG / W) + tid / W;
+    // each XCD walks one contiguous part of the segment list: the long rows of one community,
+    // which share most of their sources, meet in one L2
+    const int seg = xcd_contiguous(blockIdx.x, gridDim.x) * (kWG / W) + tid / W;
     if (seg >= A.nseg) return;
     const int tl = tid % W, gl = tl % G;
     const int f = blockIdx.y * (G * VEC) + gl * VEC;
