@@ -58,6 +58,13 @@ typedef struct {
 #define AG_LAYOUT_ORIGINAL  0   /* caller's numbering; the library permutes in and out   */
 #define AG_LAYOUT_REORDERED 1   /* rows already in plan order (see ag_permute_rows)      */
 
+/* community detection behind the reordering (Sec. 2.2, Sec. 4.2 stage 1) */
+#define AG_METHOD_LABEL_PROPAGATION 0  /* multilevel size-constrained label propagation (default)  */
+#define AG_METHOD_MODULARITY        1  /* one pass of size-constrained agglomeration, vertices in  *
+                                        * ascending degree, each joining the neighbouring community *
+                                        * with the largest integer modularity gain                  *
+                                        * conn * 2m - deg_u * deg_v                                 */
+
 #define AG_FLAG_HOST_ONLY   1   /* build the decomposition on the host only: no device   *
                                  * memory, ag_aggregate* return AG_ERR_UNSUPPORTED       */
 
@@ -91,6 +98,8 @@ typedef struct {
      * keeps the stored values.  Needs vals; AG_ERR_INVALID if an intra-community value departs   *
      * from the product by more than 1e-6 relative.                                               */
     const float *row_scale, *col_scale;
+    int32_t method;         /* community detection of the reordering, AG_METHOD_* (Sec. 4.2: the        *
+                             * partitioner is the user's choice; Sec. 6.1 compares two)                  */
 } ag_options;
 
 /* ---- plan life cycle -------------------------------------------------------------------- */

@@ -20,6 +20,7 @@ AG_OK = 0
 AG_ERR_INVALID, AG_ERR_NOMEM, AG_ERR_HIP, AG_ERR_UNSUPPORTED = -1, -2, -3, -4
 AG_LAYOUT_ORIGINAL, AG_LAYOUT_REORDERED = 0, 1
 AG_FLAG_HOST_ONLY = 1
+AG_METHOD_LABEL_PROPAGATION, AG_METHOD_MODULARITY = 0, 1
 AG_CLS_BLOCKS_DENSE, AG_CLS_BLOCKS_SPARSE, AG_CLS_REMAINDER, AG_CLS_COMPOSE = 0, 1, 2, 3
 AG_NUM_CLS = 4
 AG_K_BLOCK_SPARSE, AG_K_BLOCK_DENSE, AG_K_BLOCK_DENSE_BF16X3 = 0, 1, 2
@@ -45,7 +46,7 @@ class ag_options(C.Structure):
                 ("layout", C.c_int32),
                 ("flags", C.c_int32), ("dense_density", C.c_float),
                 ("dev_alloc", C.c_void_p), ("dev_free", C.c_void_p), ("user", C.c_void_p),
-                ("row_scale", C.c_void_p), ("col_scale", C.c_void_p)]
+                ("row_scale", C.c_void_p), ("col_scale", C.c_void_p), ("method", C.c_int32)]
 
 
 class ag_selector_info(C.Structure):

@@ -68,7 +68,7 @@ int parallel_ranges(int64_t n, Fn fn, int64_t min_per_thread = 4096)
 
 // reorder.cpp
 void build_pattern_graph(const HostCsr &A, const HostCsr &At, WGraph &g);
-void community_reorder(const WGraph &g0, int32_t cap, int32_t min_block, int32_t sweeps,
+void community_reorder(const WGraph &g0, int32_t method, int32_t cap, int32_t min_block, int32_t sweeps,
                        int32_t max_levels, int32_t order_levels, ReorderResult &out);
 
 // decompose.cpp

@@ -414,7 +414,7 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
     if (o.order_levels == 0) o.order_levels = 3;          // negative = keep the communities in id order
     if (o.trials == 0) o.trials = 3;
     if (o.block_cap < 1 || o.block_cap > kMaxBlock || o.min_block < 1 || o.sweeps < 1 || o.max_levels < 1 ||
-        o.trials < 1 || o.trials > kMaxTrials || (o.layout != AG_LAYOUT_ORIGINAL && o.layout != AG_LAYOUT_REORDERED) ||
+        o.trials < 1 || o.trials > kMaxTrials || (o.method != AG_METHOD_LABEL_PROPAGATION && o.method != AG_METHOD_MODULARITY) || (o.layout != AG_LAYOUT_ORIGINAL && o.layout != AG_LAYOUT_REORDERED) ||
         (!o.dev_alloc) != (!o.dev_free)) {
         set_error("option out of range");
         return AG_ERR_INVALID;
@@ -444,7 +444,7 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
         {
             WGraph g;
             build_pattern_graph(A0, At, g);
-            community_reorder(g, o.block_cap, o.min_block, o.sweeps, o.max_levels,
+            community_reorder(g, o.method, o.block_cap, o.min_block, o.sweeps, o.max_levels,
                               o.order_levels < 0 ? 0 : o.order_levels, t->r);
         }
         double t1 = now_sec();

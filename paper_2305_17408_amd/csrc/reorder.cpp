@@ -1,8 +1,9 @@
 // Community-based vertex reordering (paper Sec. 2.2 and Sec. 4.2, first preprocessing stage).
 //
 // The paper hands this step to an external partitioner with "community size" as its
-// parameter.  This library uses its own integer-only, deterministic method: multilevel
-// label propagation under a community-size cap.  Vertices end up grouped by community;
+// parameter.  This library uses its own integer-only, deterministic methods: multilevel
+// label propagation under a community-size cap (the default) or one pass of agglomeration
+// by modularity gain under the same cap.  Vertices end up grouped by community;
 // communities of at least `min_block` members become the diagonal blocks of the
 // intra-community subgraph, everything else is placed behind them as a block-less tail.
 #include <algorithm>
@@ -190,9 +191,80 @@ void contract(const WGraph &g, const std::vector<int32_t> &cluster, int32_t k, W
     }
 }
 
+// The second community detection (the partitioner is the user's choice, Sec. 4.2): one pass of
+// agglomeration under the size cap, vertices visited in ascending degree (a counting sort keeps
+// equal degrees in ascending id).  The visited vertex stands for the community rooted at it; it
+// joins the neighbouring community with the largest positive integer modularity gain
+//     conn * M2 - deg[u] * deg[r]        (M2 = sum of all degrees)
+// that still has room, smallest root id among equal gains.  Returns the community count and
+// fills `cluster` with dense ids numbered by first appearance in ascending vertex order.
+int32_t agglomerate(const WGraph &g, int32_t cap, std::vector<int32_t> &cluster)
+{
+    const int32_t n = g.n;
+    std::vector<int64_t> deg(n, 0);
+    int64_t M2 = 0, maxdeg = 0;
+    for (int32_t v = 0; v < n; ++v) {
+        for (int64_t e = g.xadj[v]; e < g.xadj[v + 1]; ++e) deg[v] += g.ew[e];
+        M2 += deg[v];
+        maxdeg = std::max(maxdeg, deg[v]);
+    }
+    // visiting order: by degree, then id
+    std::vector<int32_t> order(n);
+    {
+        std::vector<int64_t> first((size_t)maxdeg + 2, 0);
+        for (int32_t v = 0; v < n; ++v) first[deg[v] + 1]++;
+        for (int64_t d = 0; d <= maxdeg; ++d) first[d + 1] += first[d];
+        for (int32_t v = 0; v < n; ++v) order[first[deg[v]]++] = v;
+    }
+    std::vector<int32_t> root(n), size(g.nw);
+    std::iota(root.begin(), root.end(), 0);
+    std::vector<std::vector<int32_t>> members(n);       // of roots that absorbed somebody (the root itself excluded)
+    std::vector<int64_t> conn(n, 0);
+    std::vector<int32_t> stamp(n, -1), touched;
+    for (int32_t u : order) {
+        if (deg[u] == 0) continue;
+        touched.clear();
+        auto scan = [&](int32_t x) {
+            for (int64_t e = g.xadj[x]; e < g.xadj[x + 1]; ++e) {
+                const int32_t r = root[g.adj[e]];
+                if (r == u) continue;
+                if (stamp[r] != u) { stamp[r] = u; conn[r] = 0; touched.push_back(r); }
+                conn[r] += g.ew[e];
+            }
+        };
+        scan(u);
+        for (int32_t x : members[u]) scan(x);
+        int32_t best = -1;
+        int64_t best_gain = 0;
+        for (int32_t r : touched) {
+            if (size[u] + size[r] > cap) continue;
+            const int64_t gain = conn[r] * M2 - deg[u] * deg[r];
+            if (gain <= 0) continue;
+            if (best < 0 || gain > best_gain || (gain == best_gain && r < best)) { best = r; best_gain = gain; }
+        }
+        if (best < 0) continue;
+        std::vector<int32_t> &mb = members[best];
+        root[u] = best;
+        mb.push_back(u);
+        for (int32_t x : members[u]) { root[x] = best; mb.push_back(x); }
+        std::vector<int32_t>().swap(members[u]);
+        size[best] += size[u];
+        deg[best] += deg[u];
+    }
+    std::vector<int32_t> dense_id(n, -1);
+    int32_t k = 0;
+    cluster.resize(n);
+    for (int32_t v = 0; v < n; ++v) {
+        int32_t &d = dense_id[root[v]];
+        if (d < 0) d = k++;
+        cluster[v] = d;
+    }
+    return k;
+}
+
 }  // namespace
 
-void community_reorder(const WGraph &g0, int32_t cap, int32_t min_block, int32_t sweeps,
+void community_reorder(const WGraph &g0, int32_t method, int32_t cap, int32_t min_block, int32_t sweeps,
                        int32_t max_levels, int32_t order_levels, ReorderResult &out)
 {
     const int32_t n = g0.n;
@@ -202,6 +274,10 @@ void community_reorder(const WGraph &g0, int32_t cap, int32_t min_block, int32_t
     WGraph coarse;
     const WGraph *g = &g0;
     std::vector<int32_t> cluster;
+    if (method == AG_METHOD_MODULARITY && n > 0) {
+        n_comm = agglomerate(g0, cap, out.comm);
+        g = &coarse;                                     // empty: no propagation levels
+    }
     for (int32_t level = 0; g->n > 0;) {
         const int32_t k = propagate(*g, level, cap, sweeps, cluster);
         for (int32_t v = 0; v < n; ++v) out.comm[v] = cluster[out.comm[v]];

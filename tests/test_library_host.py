@@ -32,7 +32,7 @@ def compare_with_oracle(g, **kw):
     p = host_plan(g, **kw)
     try:
         e = ag.ag_plan_export(p)
-        okw = {k: v for k, v in kw.items() if k in ("block_cap", "min_block", "sweeps", "max_levels")}
+        okw = {k: v for k, v in kw.items() if k in ("block_cap", "min_block", "sweeps", "max_levels", "method")}
         if "order_levels" in kw:
             okw["order_levels"] = max(kw["order_levels"], 0)
         r = oracle.reorder(g.rowptr, g.colidx, **okw)
@@ -76,6 +76,20 @@ def test_decomposition_bit_exact_directed_and_small_caps():
     compare_with_oracle(from_edges(0, np.empty(0, int), np.empty(0, int)))
     compare_with_oracle(config_graph(2, scale=1 / 32), order_levels=-1)         # plain id order
     compare_with_oracle(config_graph(2, scale=1 / 32), order_levels=1)
+
+
+@pytest.mark.parametrize("cfg,scale", [(0, 1.0), (1, 1.0), (2, 1 / 16), (3, 1 / 32), (4, 1 / 32)])
+def test_modularity_gain_method_bit_exact_and_finds_communities(cfg, scale):
+    # the second community detection (Sec. 4.2: the partitioner is the user's choice)
+    g = config_graph(cfg, scale=scale)
+    st = compare_with_oracle(g, method=ag.AG_METHOD_MODULARITY)
+    assert st["n_blocks"] > 0 and st["nnz_intra"] + st["nnz_inter"] == st["nnz"]
+    if cfg in (0, 1, 3):
+        # planted partitions: well over half of the planted intra-community edges end up in blocks
+        got = (st["nnz_intra"] - st["n_block_rows"]) / 2 / g.meta["edges"]
+        assert got > 0.6 * g.meta["planted_intra_frac"], got
+    compare_with_oracle(directed_random(2000, 3.0, 9), method=ag.AG_METHOD_MODULARITY, min_block=4)
+    compare_with_oracle(g, method=ag.AG_METHOD_MODULARITY, block_cap=16, order_levels=-1)
 
 
 def test_number_of_communities_parameter():
@@ -156,6 +170,8 @@ def test_input_validation():
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n + 1, 4, flags=1))
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 0, flags=1))
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 4, flags=1, block_cap=129))
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 4, flags=1, method=2))
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 4, flags=1, trials=16))
     p = host_plan(g)
     expect_error(ag.AG_ERR_UNSUPPORTED, lambda: ag.ag_plan_force_kernels(p, ag.AG_CLS_BLOCKS_SPARSE, 0, 1))
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_force_kernels(p, 7, 0, 0))

@@ -176,7 +176,7 @@ def test_permutation_invariance_of_aggregation():
 def test_golden_trace_fixture():
     # every hand-traced case of tests/golden/reorder_traces.txt (the traces are written out there)
     from helpers import failing_reorder_traces, reorder_trace_cases
-    assert len(reorder_trace_cases()) >= 18
+    assert len(reorder_trace_cases()) >= 27
     assert failing_reorder_traces(oracle.reorder) == []
 
 

@@ -50,6 +50,18 @@ MUTANTS = {
     "ordering_cap_not_scaled": [("cap2 *= 8;", "cap2 *= 1;")],
     "ordering_levels_run_as_level_0": [("propagate_level(&cg, 1 + ol,", "propagate_level(&cg, 0,")],
     "min_block_strict": [("if (csize[c] >= min_block)", "if (csize[c] > min_block)")],
+    # second method: agglomeration by modularity gain
+    "gain_without_degree_term": [("const i64 gain = conn[r] * M2 - deg[u] * deg[r];", "const i64 gain = conn[r] * M2;")],
+    "gain_degrees_not_accumulated": [("deg[best] += deg[u];", ";")],
+    "gain_sizes_not_accumulated": [("size[best] += size[u];", ";")],
+    "gain_zero_accepted": [("if (gain > 0 && size[u] + size[r] <= cap &&", "if (gain >= 0 && size[u] + size[r] <= cap &&"),
+                           ("i64 best_gain = 0;\n        for (i32 c = 0; c < nc; ++c) {", "i64 best_gain = -1;\n        for (i32 c = 0; c < nc; ++c) {")],
+    "gain_cap_off_by_one": [("if (gain > 0 && size[u] + size[r] <= cap &&", "if (gain > 0 && size[u] + size[r] < cap &&")],
+    "gain_ties_to_largest_root": [("(gain == best_gain && r < best))) {", "(gain == best_gain && r > best))) {")],
+    "gain_m_instead_of_2m": [("const i64 gain = conn[r] * M2 - deg[u] * deg[r];", "const i64 gain = conn[r] * (M2 / 2) - deg[u] * deg[r];")],
+    "gain_visit_in_id_order": [("    if (x->deg != y->deg) return (x->deg > y->deg) - (x->deg < y->deg);\n", "")],
+    "gain_visit_in_descending_degree": [("    if (x->deg != y->deg) return (x->deg > y->deg) - (x->deg < y->deg);", "    if (x->deg != y->deg) return (x->deg < y->deg) - (x->deg > y->deg);")],
+    "gain_smallest_gain_wins": [("(gain > best_gain || (gain == best_gain && r < best))) {", "(best < 0 || gain < best_gain || (gain == best_gain && r < best))) {")],
 }
 
 
@@ -63,9 +75,9 @@ def _build(tmp_path, name, patches):
     c.write_text(text)
     subprocess.check_call(["gcc", "-O1", "-fPIC", "-shared", "-std=c11", "-o", str(so), str(c), "-lm"])
     lib = ctypes.CDLL(str(so))
-    lib.orc_reorder.restype = ctypes.c_int
+    lib.orc_reorder_method.restype = ctypes.c_int
 
-    def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels=12, order_levels=0):
+    def reorder(rowptr, colidx, *, block_cap=128, min_block=16, sweeps=8, max_levels=12, order_levels=0, method=0):
         rowptr = np.ascontiguousarray(rowptr, np.int32)
         colidx = np.ascontiguousarray(colidx, np.int32)
         n = rowptr.size - 1
@@ -73,7 +85,7 @@ def _build(tmp_path, name, patches):
         blk = np.empty(n + 1, np.int32)
         nb = ctypes.c_int32(0)
         ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
-        rc = lib.orc_reorder(ctypes.c_int64(n), ptr(rowptr), ptr(colidx), ctypes.c_int32(block_cap),
+        rc = lib.orc_reorder_method(ctypes.c_int64(n), ptr(rowptr), ptr(colidx), ctypes.c_int32(method), ctypes.c_int32(block_cap),
                              ctypes.c_int32(min_block), ctypes.c_int32(sweeps), ctypes.c_int32(max_levels),
                              ctypes.c_int32(order_levels), ptr(perm), ptr(iperm), ptr(blk), ctypes.byref(nb),
                              ptr(comm))

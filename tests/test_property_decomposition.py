@@ -36,9 +36,9 @@ def random_matrix(draw):
 
 @settings(max_examples=150, deadline=None, suppress_health_check=[HealthCheck.too_slow])
 @given(g=random_matrix(), cap=st.integers(1, 128), minb=st.integers(1, 20), sweeps=st.integers(1, 8),
-       levels=st.integers(1, 12), order=st.sampled_from([-1, 1, 2, 3]))
-def test_library_equals_oracle(g, cap, minb, sweeps, levels, order):
-    kw = dict(block_cap=cap, min_block=minb, sweeps=sweeps, max_levels=levels, order_levels=order)
+       levels=st.integers(1, 12), order=st.sampled_from([-1, 1, 2, 3]), method=st.sampled_from([0, 1]))
+def test_library_equals_oracle(g, cap, minb, sweeps, levels, order, method):
+    kw = dict(block_cap=cap, min_block=minb, sweeps=sweeps, max_levels=levels, order_levels=order, method=method)
     p = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, 4, flags=ag.AG_FLAG_HOST_ONLY, **kw)
     try:
         e = ag.ag_plan_export(p)
