@@ -10,6 +10,7 @@ from .graphs import (  # noqa: F401
     chung_lu_communities,
     mixed_density,
     directed_random,
+    rmat,
     from_edges,
     gcn_normalise,
     row_normalise,

@@ -307,6 +307,35 @@ def mixed_density(n_comm: int, comm_size: int, p_dense: float, sparse_degree: fl
     return g
 
 
+def rmat(n: int, n_edges: int, seed: int, *, a: float = 0.57, b: float = 0.19, c: float = 0.19,
+         self_loops: bool = True) -> Graph:
+    """Undirected R-MAT graph (recursive-matrix generator: every edge picks one quadrant of the
+    adjacency matrix per bit level with probabilities a, b, c, 1-a-b-c) on n vertices, the kind of
+    synthetic graph the paper sweeps over densities in Sec. 2.1.  Ids are drawn on the next power
+    of two and pairs that fall outside [0, n), loops and duplicates are drawn again until exactly
+    n_edges distinct undirected edges exist."""
+    rng = _rng(seed)
+    bits = max(1, int(np.ceil(np.log2(max(2, n)))))
+    n_edges = int(min(n_edges, n * (n - 1) // 2))
+
+    def draw(k):
+        u = np.zeros(k, dtype=np.int64)
+        v = np.zeros(k, dtype=np.int64)
+        for _ in range(bits):
+            x = rng.random(k)
+            right = ((x >= a) & (x < a + b)) | (x >= a + b + c)      # quadrants b and d: column bit set
+            down = x >= a + b                                        # quadrants c and d: row bit set
+            u = (u << 1) | down
+            v = (v << 1) | right
+        ok = (u < n) & (v < n)
+        return u[ok], v[ok]
+
+    keys = _unique_pairs(n, n_edges, draw, oversample=1.5) if n_edges else np.empty(0, np.int64)
+    g = _finish(n, keys, np.full(n, -1, dtype=np.int64), rng, shuffle=True, self_loops=self_loops)
+    g.meta.update(kind="rmat", a=a, b=b, c=c)
+    return g
+
+
 def directed_random(n: int, avg_out_degree: float, seed: int, *, self_loops: bool = True,
                     weighted: bool = True) -> Graph:
     """Uniform random *directed* graph (non-symmetric pattern and values)."""

@@ -300,7 +300,27 @@ def density_sweep():
                "choice": info["choice"]}
         log(f"[sweep] {row}")
         rem.append(row)
-    return {"F": F, "block_kernels_vs_block_density": blocks, "remainder_kernels_vs_degree": rem}
+    # (c) R-MAT graphs of 19 717 vertices over a density sweep (the graphs of the paper's format-versus-
+    # density figure, Sec. 2.1): whole-graph kernels (no blocks: min_block above the cap) and the
+    # adaptive decomposition on the same graph
+    from ag_inputs import rmat
+    n = 19717
+    rm = []
+    for dens in (1e-5, 3e-5, 1e-4, 3e-4, 1e-3, 3e-3, 1e-2, 3e-2):
+        g = rmat(n, int(dens * n * n / 2), 6000 + int(dens * 1e6))
+        info, st = trials(g, min_block=129)
+        t = info["trial_ms"]
+        info2, st2 = trials(g)
+        t2 = info2["trial_ms"][3]
+        row = {"density": dens, "n": g.n, "nnz": g.nnz, "max_degree": int(np.diff(g.rowptr).max()),
+               "csr_narrow_ms": round(t[2][0], 5), "csr_wide_ms": round(t[2][1], 5), "coo_ms": round(t[2][2], 5),
+               "decomposed_split_ms": round(t2[0], 5), "decomposed_fused_ms": round(t2[1], 5),
+               "blocks": st2["n_blocks"], "dense_class_blocks": st2["n_dense_blocks"],
+               "intra_share": round(st2["nnz_intra"] / max(1, st2["nnz"]), 4), "adaptive_choice": info2["choice"]}
+        log(f"[sweep] {row}")
+        rm.append(row)
+    return {"F": F, "block_kernels_vs_block_density": blocks, "remainder_kernels_vs_degree": rem,
+            "rmat_19717_vs_density": rm}
 
 
 def main():
@@ -315,6 +335,8 @@ def main():
                     help="skip the adaptive-versus-single-format comparison on the mixed-density workload (configs[4])")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time the other four workloads (short runs) and add them under 'other_workloads'")
+    ap.add_argument("--width", type=int, default=0,
+                    help="feature width F to run the workload's graph with instead of its own (0 = the workload's width)")
     ap.add_argument("--pin", default="",
                     help="pin the kernels instead of letting the selector choose: COMPOSE[,DENSE[,REMAINDER]] with "
                          "COMPOSE in split|fused|full|full_wide, DENSE in 0|1|2 (block-sparse, fp32 MFMA, bf16x3 MFMA), "
@@ -340,7 +362,7 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     cfg = CONFIGS[args.config]
-    F = cfg["F"]
+    F = args.width if args.width > 0 else cfg["F"]
     t0 = time.time()
     g = config_graph(args.config)
     log(f"[bench] graph {cfg['name']}: n={g.n} nnz={g.nnz} F={F} ({time.time() - t0:.1f}s)")
@@ -498,7 +520,7 @@ def main():
         del arg
 
     # ms per 2-layer GCN training step (only defined for the GCN workload)
-    if not args.no_gcn and "hidden" in cfg:
+    if not args.no_gcn and "hidden" in cfg and F == cfg["F"]:
         hid, ncls = cfg["hidden"], cfg["classes"]
         p_out = ag.ag_plan_clone_for_width(plan, ncls)
         t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
@@ -534,7 +556,7 @@ def main():
         ag.ag_plan_destroy(p_out)
 
     # ms per 5-layer GIN training step (hidden 64, 16 classes) on the unit-weight GIN workload
-    if not args.no_gcn and cfg.get("norm") == "unit":
+    if not args.no_gcn and cfg.get("norm") == "unit" and F == cfg["F"]:
         widths = [F, 64, 64, 64, 64, 16]
         L = len(widths) - 1
         by_w = {F: plan}

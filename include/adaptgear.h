@@ -70,11 +70,12 @@ typedef struct {
 
 /* All fields optional: zero selects the default. */
 typedef struct {
-    int32_t block_cap;      /* largest community / diagonal block, 1..128 (default 128; the   *
-                             * paper used 16, Sec. 2.3)                                        */
+    int32_t block_cap;      /* largest community / diagonal block, 1..256 (default 128; the   *
+                             * paper used 16, Sec. 2.3).  Blocks of more than 128 rows always  *
+                             * run the block-sparse kernel, with a larger LDS tile             */
     int32_t num_communities;/* alternative to block_cap (Sec. 4.2 lets the user give either the   *
                              * size or the number): if > 0 and block_cap == 0, the cap becomes     *
-                             * min(128, ceil(n / num_communities))                                */
+                             * min(256, ceil(n / num_communities))                                */
     int32_t min_block;      /* communities smaller than this go to the block-less tail (16, or   *
                              * the cap if that is smaller)                                        */
     int32_t sweeps;         /* label-propagation sweeps per level (8)                          */

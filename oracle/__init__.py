@@ -240,8 +240,9 @@ def gin_step(rowptr, colidx, vals, X, Ws, bs, labels, eps=0.0):
     dpre = ez / ez.sum(axis=1, keepdims=True)
     dpre[np.arange(n), labels] -= 1.0
     dpre /= n
-    dW, db = [None] * L, [None] * L
+    dW, db, dpres = [None] * L, [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
+        dpres[l] = dpre
         dW[l] = A[l].T @ dpre
         db[l] = dpre.sum(axis=0)
         if l == 0:
@@ -249,7 +250,7 @@ def gin_step(rowptr, colidx, vals, X, Ws, bs, labels, eps=0.0):
         dA = dpre @ Ws[l].T
         dH = _spmm64_t(rowptr, colidx, vals, dA) + eps * dA
         dpre = dH * (pre[l - 1] > 0.0)
-    return SimpleNamespace(Z=Z, loss=loss, dW=dW, db=db, A=A, H=H, pre=pre)
+    return SimpleNamespace(Z=Z, loss=loss, dW=dW, db=db, A=A, H=H, pre=pre, dpre=dpres)
 
 
 def _spmm64(rowptr, colidx, vals, M):

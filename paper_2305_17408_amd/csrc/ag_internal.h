@@ -12,7 +12,8 @@
 
 namespace ag {
 
-constexpr int kMaxBlock   = 128;   // rows of a diagonal block; LDS tiles are sized for it
+constexpr int kMaxBlock   = 128;   // rows of a diagonal block the dense kernels take; unit of the LDS tiles
+constexpr int kMaxBlockWide = 256; // largest diagonal block (one-byte block-local columns), block-sparse kernel only
 constexpr int kLongThresh = 96;    // remainder rows above this many entries are split ...
 constexpr int kSegLen     = 384;   // ... into segments of this many entries, one wavefront each
 
@@ -111,7 +112,7 @@ struct CsrDev {
 
 struct BlocksDev {
     const int32_t *blk_ptr = nullptr;      // nb + 1
-    int32_t nb = 0, n_block_rows = 0;
+    int32_t nb = 0, n_block_rows = 0, max_block_rows = 0;
     const int32_t *i_rowptr = nullptr;     // n_block_rows + 1 (intra entries of block rows)
     const uint8_t *i_col8 = nullptr;
     const float   *i_val = nullptr;        // nullptr = unit weights
@@ -176,6 +177,10 @@ int launch_gemm_nn_auto(int64_t N, int32_t k, int32_t n, const float *A, const f
 size_t hidden_backward_scratch_floats(int64_t N, int32_t hd, int32_t c);
 int launch_hidden_backward(int64_t N, int32_t hd, int32_t c, const float *dQ, const float *W2T, const float *H1,
                            float *dPre, float *dW2, float *scratch, void *stream);
+size_t gcn_backward_fused_scratch_floats(int64_t N, int32_t fi, int32_t hd, int32_t c);
+int launch_gcn_backward_fused(int64_t N, int32_t fi, int32_t hd, int32_t c, const float *dQ, const float *W2T,
+                              const float *H1, const float *P, float *dW1, float *db1, float *dW2, float *scratch,
+                              void *stream);
 int launch_transpose_small(int32_t rows, int32_t cols, const float *in, float *out, void *stream);
 
 // api.cpp

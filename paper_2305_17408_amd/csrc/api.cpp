@@ -125,6 +125,8 @@ struct Topology {
         B.blk_ptr = blk_ptr_dev;
         B.nb = r.n_blocks;
         B.n_block_rows = r.blk_ptr.back();
+        B.max_block_rows = 0;
+        for (int32_t b = 0; b < r.n_blocks; ++b) B.max_block_rows = std::max(B.max_block_rows, r.blk_ptr[b + 1] - r.blk_ptr[b]);
         std::vector<int32_t> irp(H.intra.rowptr.begin(), H.intra.rowptr.begin() + B.n_block_rows + 1);
         if ((rc = upload(irp, B.i_rowptr))) return rc;
         if ((rc = upload(H.intra_col8, B.i_col8))) return rc;
@@ -406,14 +408,14 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
     if (opt_in) o = *opt_in;
     if (o.num_communities < 0) { set_error("option out of range"); return AG_ERR_INVALID; }
     if (o.block_cap == 0 && o.num_communities > 0)
-        o.block_cap = (int32_t)std::max<int64_t>(1, std::min<int64_t>(kMaxBlock, (N + o.num_communities - 1) / o.num_communities));
+        o.block_cap = (int32_t)std::max<int64_t>(1, std::min<int64_t>(kMaxBlockWide, (N + o.num_communities - 1) / o.num_communities));
     if (o.block_cap == 0) o.block_cap = kMaxBlock;
     if (o.min_block == 0) o.min_block = std::min(16, o.block_cap);
     if (o.sweeps == 0) o.sweeps = 8;
     if (o.max_levels == 0) o.max_levels = 12;
     if (o.order_levels == 0) o.order_levels = 3;          // negative = keep the communities in id order
     if (o.trials == 0) o.trials = 3;
-    if (o.block_cap < 1 || o.block_cap > kMaxBlock || o.min_block < 1 || o.sweeps < 1 || o.max_levels < 1 ||
+    if (o.block_cap < 1 || o.block_cap > kMaxBlockWide || o.min_block < 1 || o.sweeps < 1 || o.max_levels < 1 ||
         o.trials < 1 || o.trials > kMaxTrials || (o.method != AG_METHOD_LABEL_PROPAGATION && o.method != AG_METHOD_MODULARITY) || (o.layout != AG_LAYOUT_ORIGINAL && o.layout != AG_LAYOUT_REORDERED) ||
         (!o.dev_alloc) != (!o.dev_free)) {
         set_error("option out of range");
@@ -477,7 +479,8 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
             const int32_t r0 = t->r.blk_ptr[b], r1 = t->r.blk_ptr[b + 1];
             const double sz = r1 - r0, cnt = I.rowptr[r1] - I.rowptr[r0];
             t->all_blocks.push_back(b);
-            if (cnt >= o.dense_density * sz * sz && sz >= 32) t->dense_blocks.push_back(b);
+            // the dense kernels take blocks of 32 to 128 rows (four wavefronts of 32 rows, 128-bit row maps)
+            if (cnt >= o.dense_density * sz * sz && sz >= 32 && sz <= kMaxBlock) t->dense_blocks.push_back(b);
             else t->sparse_blocks.push_back(b);
         }
         const int ndir = t->symmetric ? 1 : 2;

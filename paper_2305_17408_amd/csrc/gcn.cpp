@@ -39,8 +39,9 @@ size_t ws_floats(int64_t n, int32_t fi, int32_t hd, int32_t c)
 {
     return pad4((size_t)n * fi) + 2 * pad4((size_t)n * hd) + 4 * pad4((size_t)n * c) + pad4((size_t)n) +
            pad4((size_t)hd * c) + pad4(wsplit_floats(fi, hd, c)) +
-           std::max(std::max(col_sum_scratch_floats(std::max(hd, c)), hidden_backward_scratch_floats(n, hd, c)),
-                    std::max(gemm_tn_scratch_floats(fi, hd), gemm_tn_scratch_floats(hd, c))) + 64;
+           std::max(std::max(std::max(col_sum_scratch_floats(std::max(hd, c)), hidden_backward_scratch_floats(n, hd, c)),
+                             std::max(gemm_tn_scratch_floats(fi, hd), gemm_tn_scratch_floats(hd, c))),
+                    gcn_backward_fused_scratch_floats(n, fi, hd, c)) + 64;
 }
 
 }  // namespace
@@ -102,7 +103,10 @@ int ag_gcn_step(ag_plan *p_in, ag_plan *p_out, const ag_gcn_io *io, const float 
     if ((rc = launch_col_sum(n, c, w.dZ, io->db2, w.scratch, stream))) return rc;
     if ((rc = ag_aggregate_t(p_out, w.dZ, w.dQ, stream))) return rc;                           // dQ = A^T dZ
     if ((rc = launch_transpose_small(hd, c, io->W2, w.W2T, stream))) return rc;
-    // dW2 = H1^T dQ and dPre = (dQ W2^T) * (H1 > 0): one fused pass where the shape allows it
+    // dW2, dW1 and db1 in one pass over P, H1 and dQ, dPre never leaving the registers, where the shape allows it
+    rc = launch_gcn_backward_fused(n, fi, hd, c, w.dQ, w.W2T, w.H1, w.P, io->dW1, io->db1, io->dW2, w.scratch, stream);
+    if (rc != AG_ERR_UNSUPPORTED) return rc;
+    // otherwise dW2 = H1^T dQ and dPre = (dQ W2^T) * (H1 > 0) in one fused pass where the shape allows that
     rc = launch_hidden_backward(n, hd, c, w.dQ, w.W2T, w.H1, w.dH1, io->dW2, w.scratch, stream);
     if (rc == AG_ERR_UNSUPPORTED) {
         if ((rc = launch_gemm_tn(n, hd, c, w.H1, w.dQ, io->dW2, nullptr, w.scratch, stream))) return rc;

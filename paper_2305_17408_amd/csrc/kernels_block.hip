@@ -24,7 +24,7 @@ namespace {
 // Entries lo..hi-1 of a register chunk (lane k of the team holds entry k); feature rows come
 // from the LDS tile.  Entries beyond hi belong to other rows: they are redirected to the zero
 // row of the tile with weight 0, so nothing of them reaches the sum (not even 0 * Inf).
-template <int G, int NV, int VEC>
+template <int G, int NV, int VEC, int MAXR>
 __device__ __forceinline__ void chunk_range_lds(int c, float v, int lo, int hi, const float *sH, int gl,
                                                 float (&acc)[NV][VEC])
 {
@@ -37,7 +37,7 @@ __device__ __forceinline__ void chunk_range_lds(int c, float v, int lo, int hi, 
             const bool ok = k0 + u < hi;
             const int ck = __shfl(c, (k0 + u) & (G - 1), G);
             const float vk = __shfl(v, (k0 + u) & (G - 1), G);
-            row[u] = ok ? ck : kMaxBlock;
+            row[u] = ok ? ck : MAXR;                    // the zero row behind the tile
             w[u] = ok ? vk : 0.f;
         }
 #pragma unroll
@@ -53,14 +53,15 @@ __device__ __forceinline__ void chunk_range_lds(int c, float v, int lo, int hi, 
     }
 }
 
-template <int G, int NV, int VEC, bool FUSED, bool SCALED>
+template <int G, int NV, int VEC, bool FUSED, bool SCALED, int MAXR>
 __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t *__restrict__ list,
                                                       CsrDev R, const float *__restrict__ H,
                                                       float *__restrict__ Y, int F)
 {
     constexpr int FT = G * VEC * NV, TEAMS = kWG / G;
     static_assert(kMaxBlock / TEAMS + 1 <= G, "row pointers of a team must fit in its lanes");
-    extern __shared__ float sH[];                       // (kMaxBlock + 1) x FT: feature tile + a zero row
+    static_assert(MAXR % kMaxBlock == 0 && MAXR <= 256, "one-byte block-local columns");
+    extern __shared__ float sH[];                       // (MAXR + 1) x FT: feature tile + a zero row
     const int tid = threadIdx.x;
     const int b = list[xcd_contiguous(blockIdx.x, gridDim.x)];   // neighbouring blocks share an XCD (L2)
     const int r0 = B.blk_ptr[b], nr = B.blk_ptr[b + 1] - r0;
@@ -70,16 +71,12 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
     bool fok[NV];
 #pragma unroll
     for (int q = 0; q < NV; ++q) fok[q] = f + q * G * VEC < F;
-    const int rpt = (nr + TEAMS - 1) / TEAMS;           // rows per team
-    const int first = min(team * rpt, nr);
-    const int myrows = min(rpt, nr - first);
-    const int irp = B.i_rowptr[r0 + first + min(gl, myrows)];
-    // factored values: lane gl keeps the output factor of the team's row gl (fetched with the row pointers)
-    const float osc = (SCALED && B.out_scale && gl < myrows) ? B.out_scale[r0 + first + gl] : 1.f;
-    const int ie1 = __shfl(irp, myrows, G);
-    int iq = __shfl(irp, 0, G);                         // entry held by lane 0 of ring chunk 0
-    int ic0, ic1, ic2;
-    float iv0, iv1, iv2;
+    // The block's rows are served in runs of kMaxBlock (blocks of up to 128 rows: one run); within a
+    // run every team takes a contiguous share of the rows.  State of the team for the current run:
+    int first, myrows, irp, ie1, iq, ic0, ic1, ic2;
+    float osc, iv0, iv1, iv2;
+    int rrp = 0, re1 = 0, rq = 0, rc0 = 0, rc1 = 0, rc2 = 0;
+    float rv0 = 0.f, rv1 = 0.f, rv2 = 0.f;
     auto ld_i = [&](int e, int &c, float &v) {
         c = 0;
         v = 0.f;
@@ -88,11 +85,6 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
             v = B.i_val ? B.i_val[e] : 1.f;
         }
     };
-    ld_i(iq + gl, ic0, iv0);
-    ld_i(iq + G + gl, ic1, iv1);
-    ld_i(iq + 2 * G + gl, ic2, iv2);
-    int rrp = 0, re1 = 0, rq = 0, rc0 = 0, rc1 = 0, rc2 = 0;
-    float rv0 = 0.f, rv1 = 0.f, rv2 = 0.f;
     auto ld_r = [&](int e, int &c, float &v) {
         c = 0;
         v = 0.f;
@@ -101,17 +93,33 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
             v = R.val ? R.val[e] : 1.f;
         }
     };
-    if constexpr (FUSED) {
-        rrp = R.rowptr[r0 + first + min(gl, myrows)];
-        re1 = __shfl(rrp, myrows, G);
-        rq = __shfl(rrp, 0, G);
-        ld_r(rq + gl, rc0, rv0);
-        ld_r(rq + G + gl, rc1, rv1);
-        ld_r(rq + 2 * G + gl, rc2, rv2);
-    }
-    stage_tile<FT, VEC>(H, F, r0, nr, nr, f0, sH, tid, SCALED ? B.in_scale : nullptr);
-    for (int j = tid; j < FT; j += kWG) sH[kMaxBlock * FT + j] = 0.f;
+    auto begin_run = [&](int c0) {                      // row pointers and the first topology chunks of a run
+        const int cn = min(kMaxBlock, nr - c0);
+        const int rpt = (cn + TEAMS - 1) / TEAMS;       // rows per team
+        first = c0 + min(team * rpt, cn);
+        myrows = min(rpt, c0 + cn - first);
+        irp = B.i_rowptr[r0 + first + min(gl, myrows)];
+        // factored values: lane gl keeps the output factor of the team's row gl (fetched with the row pointers)
+        osc = (SCALED && B.out_scale && gl < myrows) ? B.out_scale[r0 + first + gl] : 1.f;
+        ie1 = __shfl(irp, myrows, G);
+        iq = __shfl(irp, 0, G);                         // entry held by lane 0 of ring chunk 0
+        ld_i(iq + gl, ic0, iv0);
+        ld_i(iq + G + gl, ic1, iv1);
+        ld_i(iq + 2 * G + gl, ic2, iv2);
+        if constexpr (FUSED) {
+            rrp = R.rowptr[r0 + first + min(gl, myrows)];
+            re1 = __shfl(rrp, myrows, G);
+            rq = __shfl(rrp, 0, G);
+            ld_r(rq + gl, rc0, rv0);
+            ld_r(rq + G + gl, rc1, rv1);
+            ld_r(rq + 2 * G + gl, rc2, rv2);
+        }
+    };
+    begin_run(0);
+    stage_tile<FT, VEC, MAXR>(H, F, r0, nr, nr, f0, sH, tid, SCALED ? B.in_scale : nullptr);
+    for (int j = tid; j < FT; j += kWG) sH[MAXR * FT + j] = 0.f;
     __syncthreads();
+    for (int c0 = 0;;) {
     for (int i = 0; i < myrows; ++i) {
         const int row = r0 + first + i;
         float acc[NV][VEC];
@@ -129,7 +137,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
                     ld_i(iq + 2 * G + gl, ic2, iv2);
                 }
                 const int hi = min(re, iq + G) - iq;
-                chunk_range_lds<G, NV, VEC>(ic0, iv0, k - iq, hi, sH, gl, acc);
+                chunk_range_lds<G, NV, VEC, MAXR>(ic0, iv0, k - iq, hi, sH, gl, acc);
                 k = iq + hi;
             }
         }
@@ -163,23 +171,31 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
         }
 #pragma unroll
         for (int q = 0; q < NV; ++q)
+#if defined(AG_EXP_NT) && (AG_EXP_NT & 1)
+            if (fok[q]) store_vec_nt<VEC>(Y + (size_t)row * F + f + q * G * VEC, acc[q]);
+#else
             if (fok[q]) store_vec<VEC>(Y + (size_t)row * F + f + q * G * VEC, acc[q]);
+#endif
+    }
+    c0 += kMaxBlock;
+    if (MAXR == kMaxBlock || c0 >= nr) break;           // uniform over the work-group
+    begin_run(c0);
     }
 }
 
-template <int G, int NV, int VEC, bool FUSED, bool SCALED>
+template <int G, int NV, int VEC, bool FUSED, bool SCALED, int MAXR>
 int launch_one(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev &R, const float *H, float *Y,
                int F, hipStream_t st)
 {
     constexpr int FT = G * VEC * NV;
-    constexpr size_t lds = (size_t)(kMaxBlock + 1) * FT * sizeof(float);
+    constexpr size_t lds = (size_t)(MAXR + 1) * FT * sizeof(float);
     if (lds > 65536) {
         // more than the default 64 KB of dynamic LDS has to be requested once per device
         static std::atomic<bool> prepared[64];          // per instantiation and device
         int dev = 0;
         (void)hipGetDevice(&dev);
         if (dev < 0 || dev >= 64 || !prepared[dev].load(std::memory_order_acquire)) {
-            int rc = hip_fail((int)hipFuncSetAttribute((const void *)k_block_sparse<G, NV, VEC, FUSED, SCALED>,
+            int rc = hip_fail((int)hipFuncSetAttribute((const void *)k_block_sparse<G, NV, VEC, FUSED, SCALED, MAXR>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
                               "LDS size attribute");
             if (rc) return rc;
@@ -187,19 +203,28 @@ int launch_one(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev 
         }
     }
     dim3 grid(nlist, (F + FT - 1) / FT);
-    hipLaunchKernelGGL((k_block_sparse<G, NV, VEC, FUSED, SCALED>), grid, dim3(kWG), lds, st, B, list, R, H, Y, F);
+    hipLaunchKernelGGL((k_block_sparse<G, NV, VEC, FUSED, SCALED, MAXR>), grid, dim3(kWG), lds, st, B, list, R, H, Y, F);
     return hip_fail((int)hipGetLastError(), "block_sparse launch");
 }
 
+template <int G, int NV, int VEC, int MAXR>
+int run_sized(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev *rem, const float *H,
+              float *Y, int F, hipStream_t st)
+{
+    const bool scaled = B.in_scale || B.out_scale;      // factored values: a separate instantiation keeps the plain path lean
+    if (rem) return scaled ? launch_one<G, NV, VEC, true, true, MAXR>(B, list, nlist, *rem, H, Y, F, st)
+                           : launch_one<G, NV, VEC, true, false, MAXR>(B, list, nlist, *rem, H, Y, F, st);
+    return scaled ? launch_one<G, NV, VEC, false, true, MAXR>(B, list, nlist, CsrDev(), H, Y, F, st)
+                  : launch_one<G, NV, VEC, false, false, MAXR>(B, list, nlist, CsrDev(), H, Y, F, st);
+}
+
+// plans whose blocks all have at most 128 rows keep the smaller LDS tile (more work-groups per CU)
 template <int G, int NV, int VEC>
 int run(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev *rem, const float *H,
         float *Y, int F, hipStream_t st)
 {
-    const bool scaled = B.in_scale || B.out_scale;      // factored values: a separate instantiation keeps the plain path lean
-    if (rem) return scaled ? launch_one<G, NV, VEC, true, true>(B, list, nlist, *rem, H, Y, F, st)
-                           : launch_one<G, NV, VEC, true, false>(B, list, nlist, *rem, H, Y, F, st);
-    return scaled ? launch_one<G, NV, VEC, false, true>(B, list, nlist, CsrDev(), H, Y, F, st)
-                  : launch_one<G, NV, VEC, false, false>(B, list, nlist, CsrDev(), H, Y, F, st);
+    if (B.max_block_rows > kMaxBlock) return run_sized<G, NV, VEC, kMaxBlockWide>(B, list, nlist, rem, H, Y, F, st);
+    return run_sized<G, NV, VEC, kMaxBlock>(B, list, nlist, rem, H, Y, F, st);
 }
 
 }  // namespace

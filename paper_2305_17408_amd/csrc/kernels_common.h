@@ -23,6 +23,32 @@ __device__ __forceinline__ void load_vec(const float *__restrict__ p, float (&h)
     }
 }
 
+#ifdef AG_EXP_NT
+template <int VEC>
+__device__ __forceinline__ void load_vec_nt(const float *__restrict__ p, float (&h)[VEC])
+{
+    if constexpr (VEC == 4) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
+        h[0] = t.x; h[1] = t.y; h[2] = t.z; h[3] = t.w;
+    } else {
+        load_vec<VEC>(p, h);
+    }
+}
+template <int VEC>
+__device__ __forceinline__ void store_vec_nt(float *__restrict__ p, const float (&h)[VEC])
+{
+    if constexpr (VEC == 4) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        f4 t = {h[0], h[1], h[2], h[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<f4 *>(p));
+    } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) p[j] = h[j];
+    }
+}
+#endif
+
 template <int VEC>
 __device__ __forceinline__ void store_vec(float *__restrict__ p, const float (&h)[VEC])
 {
@@ -54,12 +80,12 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int nb)
 // thread are issued before its first LDS store, so a tile costs one memory latency, not one per
 // row.  With `scale` every row is multiplied by scale[row] on the way (factored edge values).
 // Must be called by the whole work-group; the caller synchronises afterwards.
-template <int FT, int VEC>
+template <int FT, int VEC, int MAXR = kMaxBlock>
 __device__ __forceinline__ void stage_tile(const float *__restrict__ H, int F, int r0, int nr, int pad_rows,
                                            int f0, float *sH, int tid, const float *__restrict__ scale = nullptr)
 {
     constexpr int UPR = FT / VEC;                       // load units per tile row
-    constexpr int ITER = (kMaxBlock * UPR + kWG - 1) / kWG;
+    constexpr int ITER = (MAXR * UPR + kWG - 1) / kWG;  // the tile holds at most MAXR rows
     float h[ITER][VEC];
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
@@ -169,7 +195,11 @@ __device__ __forceinline__ void chunk_range_global(int c, float v, int lo, int h
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
                 if (k0 + u < hi && fok[q]) {
+#if defined(AG_EXP_NT) && (AG_EXP_NT & 2)
+                    load_vec_nt<VEC>(H + (size_t)ck[u] * F + f + q * G * VEC, h[u][q]);
+#else
                     load_vec<VEC>(H + (size_t)ck[u] * F + f + q * G * VEC, h[u][q]);
+#endif
                 } else {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) h[u][q][j] = 0.f;

@@ -638,6 +638,156 @@ __global__ __launch_bounds__(kWG) void k_hidden_backward_mfma(const float *__res
     }
 }
 
+// The whole backward pass through the two dense transforms of a two-layer GCN in ONE pass over
+// P, H1 and dQ, without ever writing dPre (N x hd) to memory:
+//     dPre = (dQ W2^T) * (H1 > 0)       stays in registers
+//     dW2 += H1^T dQ,   dW1 += P^T dPre,   db1 += column sums of dPre
+// Same decomposition as k_hidden_backward_mfma (a wavefront owns 32 hidden columns and walks blocks
+// of 32 rows; the dPre tile comes out in the result layout of the fp32 matrix instruction).  That
+// tile is at once the B operand of the dW1 product: its k index runs over the block's rows in the
+// order the result registers hold them (step s: row 8 (s / 4) + 4 (l >> 5) + (s & 3)), and the A
+// operands P^T of that step are one contiguous load of P[that row][FI32 (l & 31) ...] per lane.
+// FI32 = f_in / 32 row tiles of dW1 per wavefront.  Every wavefront ends with its partial of
+// dW1[:, 32 columns], dW2[32 rows, :] and db1[32 columns]; fixed-order sums follow.
+template <int FI32>
+struct FusedBlock {                                  // everything one wavefront reads of a block of 32 rows
+    float q[16];                                     // the lane's row of dQ (A operand of the dPre product)
+    float b2[16];                                    // dQ in B-operand layout for the dW2 product
+    float h[16];                                     // H1 in the result layout of the instruction
+    float a[16][FI32];                               // P^T operands of the 16 k-steps of the dW1 product
+};
+
+template <int FI32>
+__global__ __launch_bounds__(kWG, 1) void k_gcn_backward_fused(const float *__restrict__ dQ, const float *__restrict__ W2T,
+                                                            const float *__restrict__ H1, const float *__restrict__ P,
+                                                            float *__restrict__ part_w1, float *__restrict__ part_w2,
+                                                            float *__restrict__ part_b1, int64_t N, int c, int hd,
+                                                            int rows_per_wg)
+{
+    constexpr int fi = FI32 * 32;
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    const int CS = min(hd / 32, 4), RS = 4 / CS;         // column slices per work-group; row sub-blocks per pass
+    const int slice = w % CS, rsub = w / CS;
+    const int col0 = blockIdx.y * 128 + slice * 32;
+    float bw[8];                                         // B operand of the dPre product: W2T[2 s + hi][col0 + lo]
+#pragma unroll
+    for (int s = 0; s < 8; ++s) bw[s] = (2 * s + hi < c) ? W2T[(size_t)(2 * s + hi) * hd + col0 + lo] : 0.f;
+    floatx16 acc2, acc1[FI32];
+    float cs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc2[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < FI32; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc1[i][r] = 0.f;
+    const int64_t rb = (int64_t)blockIdx.x * rows_per_wg, re = min(N, rb + rows_per_wg);
+    const bool c16 = (c == 16);
+    // Loads are unconditional (addresses clamped into the arrays, values selected afterwards): a
+    // load under a branch would force the following wait to drain ALL outstanding loads, the next
+    // block's included.  Row tile i of dW1 takes the features FI32 * lane + i, so the P^T operands
+    // of all FI32 tiles of one k-step are ONE contiguous load of FI32 floats per lane.
+    const int qc = min(lo, c - 1);
+    auto load = [&](FusedBlock<FI32> &B, int64_t R0) {
+        {
+            const int64_t row = min(R0 + lo, N - 1);
+            if (c16) {
+#pragma unroll
+                for (int j4 = 0; j4 < 4; ++j4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(dQ + row * 16 + 4 * j4);
+                    B.q[4 * j4] = v.x; B.q[4 * j4 + 1] = v.y; B.q[4 * j4 + 2] = v.z; B.q[4 * j4 + 3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) B.q[j] = dQ[row * c + min(j, c - 1)];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = min(R0 + 8 * (r >> 2) + 4 * hi + (r & 3), N - 1);
+            B.h[r] = H1[row * hd + col0 + lo];
+            B.b2[r] = dQ[row * c + qc];
+            load_vec<FI32 == 3 ? 1 : FI32>(P + row * fi + FI32 * lo, reinterpret_cast<float (&)[FI32 == 3 ? 1 : FI32]>(B.a[r][0]));
+            if constexpr (FI32 == 3) { B.a[r][1] = P[row * fi + 3 * lo + 1]; B.a[r][2] = P[row * fi + 3 * lo + 2]; }
+        }
+    };
+    // values of rows beyond the end of the work-group's range, and of classes beyond c, count as 0
+    auto mask = [&](FusedBlock<FI32> &B, int64_t R0) {
+        const bool rq = R0 + lo < re;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) B.q[j] = (rq && j < c) ? B.q[j] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool ok = R0 + 8 * (r >> 2) + 4 * hi + (r & 3) < re;
+            B.h[r] = ok ? B.h[r] : 0.f;
+            B.b2[r] = (ok && lo < c) ? B.b2[r] : 0.f;
+#pragma unroll
+            for (int i = 0; i < FI32; ++i) B.a[r][i] = ok ? B.a[r][i] : 0.f;
+        }
+    };
+    auto compute = [&](const FusedBlock<FI32> &B) {
+        floatx16 d;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) d[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) d = __builtin_amdgcn_mfma_f32_32x32x2f32(hi ? B.q[2 * s + 1] : B.q[2 * s], bw[s], d, 0, 0, 0);
+#pragma unroll
+        for (int s = 0; s < 16; ++s) acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(B.h[s], B.b2[s], acc2, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {                   // ReLU mask; rows beyond the end hold h = 0
+            d[r] = B.h[r] > 0.f ? d[r] : 0.f;
+            cs += d[r];
+        }
+        // dW1[32 i .. 32 i + 31][col0 .. col0 + 31] += P^T dPre: step s takes the row that register s holds
+#pragma unroll
+        for (int s = 0; s < 16; ++s)
+#pragma unroll
+            for (int i = 0; i < FI32; ++i)
+                acc1[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(B.a[s][i], d[s], acc1[i], 0, 0, 0);
+    };
+    {
+        // One wavefront per SIMD with two register sets: all loads of the next block are in flight
+        // while the 24 + 16 FI32 matrix instructions of the current block run.  The next block is
+        // always requested, also behind the last one (clamped addresses make that harmless): no
+        // branch may sit between a block's loads and the work on the block before it.
+        FusedBlock<FI32> A, B;
+        const int64_t step = 32 * RS;
+        int64_t R0 = rb + 32 * rsub;
+        if (R0 < re) {                                   // uniform over the wavefront
+            load(A, R0);
+            for (;;) {
+                load(B, R0 + step);
+                mask(A, R0);
+                compute(A);
+                R0 += step;
+                if (R0 >= re) break;
+                load(A, R0 + step);
+                mask(B, R0);
+                compute(B);
+                R0 += step;
+                if (R0 >= re) break;
+            }
+        }
+    }
+    const size_t pidx = (size_t)blockIdx.x * RS + rsub;  // partial shared by the wavefronts (and the work-groups
+                                                         // of the other column halves) that walked these rows
+    float *o2 = part_w2 + pidx * hd * c;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int m = col0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+        if (lo < c) o2[(size_t)m * c + lo] = acc2[r];
+    }
+    float *o1 = part_w1 + pidx * fi * hd;
+#pragma unroll
+    for (int i = 0; i < FI32; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = FI32 * (8 * (r >> 2) + 4 * hi + (r & 3)) + i;    // the feature that row of tile i stands for
+            o1[(size_t)m * hd + col0 + lo] = acc1[i][r];
+        }
+    const float t = cs + __shfl_xor(cs, 32);
+    if (hi == 0) part_b1[pidx * hd + col0 + lo] = t;
+}
+
 inline bool hidden_backward_on_mfma(int32_t hd, int32_t c) { return (hd == 64 || hd == 128 || hd == 256) && c >= 1 && c <= 16; }
 
 constexpr int kHiddenRowsPerWg = 1024;
@@ -758,6 +908,51 @@ int launch_hidden_backward(int64_t N, int32_t hd, int32_t c, const float *dQ, co
     hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 31) / 32)), dim3(kWG), 0, st, wgs, wgs, count,
                        scratch, dW2);
     return hip_fail((int)hipGetLastError(), "hidden_backward launch");
+}
+
+// Fused backward through both transforms of a two-layer GCN: dW2 = H1^T dQ, dW1 = P^T dPre and
+// db1 = column sums of dPre with dPre = (dQ W2T) * (H1 > 0) kept in registers.  Shapes served:
+// hidden width 64, 128 or 256, at most 16 classes, f_in in {32, 64, 96, 128}; AG_ERR_UNSUPPORTED
+// otherwise (the caller then runs the separate kernels).
+constexpr int kFusedRowsPerWg = 4096;
+
+inline bool gcn_backward_fused_ok(int32_t fi, int32_t hd, int32_t c)
+{
+    return hidden_backward_on_mfma(hd, c) && fi >= 32 && fi <= 128 && fi % 32 == 0;
+}
+
+size_t gcn_backward_fused_scratch_floats(int64_t N, int32_t fi, int32_t hd, int32_t c)
+{
+    if (!gcn_backward_fused_ok(fi, hd, c)) return 0;
+    const size_t parts = (size_t)((N + kFusedRowsPerWg - 1) / kFusedRowsPerWg) * (hd == 64 ? 2 : 1);
+    const size_t stage2 = parts > (size_t)kMaxChunks ? (parts + kSumGroup - 1) / kSumGroup : 0;
+    return parts * ((size_t)fi * hd + (size_t)hd * c + hd) + stage2 * (size_t)fi * hd + 64;
+}
+
+int launch_gcn_backward_fused(int64_t N, int32_t fi, int32_t hd, int32_t c, const float *dQ, const float *W2T,
+                              const float *H1, const float *P, float *dW1, float *db1, float *dW2, float *scratch,
+                              void *stream)
+{
+    if (!gcn_backward_fused_ok(fi, hd, c)) return AG_ERR_UNSUPPORTED;
+    if (N <= 0) return AG_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    const int wgs = (int)((N + kFusedRowsPerWg - 1) / kFusedRowsPerWg);
+    const int parts = wgs * (hd == 64 ? 2 : 1);
+    float *p1 = scratch, *p2 = p1 + (size_t)parts * fi * hd, *pb = p2 + (size_t)parts * hd * c;
+    float *stage2 = parts > kMaxChunks ? pb + (size_t)parts * hd : nullptr;
+    const dim3 grid(wgs, hd == 256 ? 2 : 1);
+#define AG_FUSED(t) hipLaunchKernelGGL((k_gcn_backward_fused<t>), grid, dim3(kWG), 0, st, dQ, W2T, H1, P, p1, p2, pb, N, c, hd, kFusedRowsPerWg)
+    switch (fi / 32) {
+    case 1: AG_FUSED(1); break;
+    case 2: AG_FUSED(2); break;
+    case 3: AG_FUSED(3); break;
+    default: AG_FUSED(4); break;
+    }
+#undef AG_FUSED
+    sum_partials(parts, (int64_t)fi * hd, p1, dW1, stage2, st);
+    sum_partials(parts, (int64_t)hd * c, p2, dW2, stage2, st);
+    sum_partials(parts, (int64_t)hd, pb, db1, stage2, st);
+    return hip_fail((int)hipGetLastError(), "gcn_backward_fused launch");
 }
 
 int launch_transpose_small(int32_t rows, int32_t cols, const float *in, float *out, void *stream)

@@ -34,6 +34,27 @@ def test_odd_widths_with_dense_class_blocks(F):
     c2.close()
 
 
+@pytest.mark.parametrize("F", [16, 64, 100, 128, 31])
+def test_blocks_of_up_to_256_rows(F):
+    # planted communities of 200 and of 256 vertices with block_cap 256: diagonal blocks beyond 128
+    # rows (the block-sparse kernel's larger LDS tile, two runs of rows per block), next to a
+    # dense-class candidate that has to stay at 128 rows or fewer; weighted and unit, every combination
+    import numpy as np
+    from ag_inputs import planted_partition, gcn_normalise, mixed_density
+    for g in (gcn_normalise(planted_partition(9, 200, 14, 0.85, 21)), planted_partition(5, 256, 30, 0.9, 22)):
+        c = Case(g, F, seed=F, block_cap=256, layout=ag.AG_LAYOUT_REORDERED)
+        sizes = np.diff(c.exp["blk_ptr"])
+        say(f"  F={F} blocks {sizes.tolist()}")
+        assert sizes.max() > 128 and sizes.max() <= 256
+        c.check_all_combos()
+        c.close()
+    g = mixed_density(4, 128, 0.3, 6, 0.0, 23)           # isolated dense communities: dense-class blocks (<= 128 rows) under a cap of 256
+    c = Case(g, F, seed=F + 1, block_cap=256)
+    assert ag.ag_plan_stats(c.plan)["n_dense_blocks"] > 0
+    c.check_all_combos()
+    c.close()
+
+
 def test_no_blocks_at_all_and_tiny_graphs():
     # uniform sparse graph with a high min_block: every vertex lands in the tail
     g = directed_random(4000, 3.0, 79)

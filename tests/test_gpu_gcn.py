@@ -47,12 +47,18 @@ def run_step(g, fin, hid, ncls, seed=0, zero=False):
 
 
 def compare(got, ref, perm):
+    """Loss to 1e-5 relative, logits to 1e-4 of their largest value, and every gradient entry to the
+    band of the aggregation itself: |g - g_ref| <= 1e-5 * sum|terms| + 1e-7, the terms being those
+    of the contraction that produces the entry (from the oracle's intermediates)."""
     assert abs(got["loss"] - ref.loss) <= 1e-5 * abs(ref.loss), (got["loss"], ref.loss)
     np.testing.assert_allclose(got["Z"], ref.Z[perm], rtol=0, atol=1e-4 * np.abs(ref.Z).max())
-    for k in ("dW1", "db1", "dW2", "db2"):
-        r = getattr(ref, k)
-        err = np.abs(got[k] - r).max()
-        assert err <= 1e-4 * np.abs(r).max(), (k, err, np.abs(r).max())
+    terms = {"dW1": np.abs(ref.P).T @ np.abs(ref.dpre1), "db1": np.abs(ref.dpre1).sum(0),
+             "dW2": np.abs(ref.H1).T @ np.abs(ref.dQ), "db2": np.abs(ref.dZ).sum(0)}
+    for k, S in terms.items():
+        err = np.abs(got[k] - getattr(ref, k))
+        ratio = float((err / (1e-5 * S + 1e-7)).max())
+        say(k, "max err", err.max(), "worst err/bound", ratio)
+        assert np.isfinite(got[k]).all() and ratio <= 1.0, (k, ratio)
 
 
 def test_gcn_step_small_nonsymmetric():
@@ -95,12 +101,4 @@ def test_gcn_step_full_size_config3():
     say(f"full-size GCN step: n={g.n} nnz={g.nnz}")
     got, ref, perm = run_step(g, 128, 256, 16)
     say("loss", got["loss"], ref.loss)
-    assert abs(got["loss"] - ref.loss) <= 1e-5 * abs(ref.loss)
-    np.testing.assert_allclose(got["Z"], ref.Z[perm], rtol=0, atol=1e-4 * np.abs(ref.Z).max())
-    terms = {"dW1": np.abs(ref.P).T @ np.abs(ref.dpre1), "db1": np.abs(ref.dpre1).sum(0),
-             "dW2": np.abs(ref.H1).T @ np.abs(ref.dQ), "db2": np.abs(ref.dZ).sum(0)}
-    for k, S in terms.items():
-        err = np.abs(got[k] - getattr(ref, k))
-        ratio = float((err / (1e-5 * S + 1e-7)).max())
-        say(k, "max err", err.max(), "worst err/bound", ratio)
-        assert ratio <= 1.0, (k, ratio)
+    compare(got, ref, perm)

@@ -51,12 +51,20 @@ def run_step(g, widths, eps=0.0, seed=0, zero=False, wscale=1.0):
 
 
 def compare(got, ref, perm):
+    """Loss to 1e-5 relative, logits to 1e-4 of their largest value, and every gradient entry to the
+    band of the aggregation itself, once per layer of the chain it went through: an entry of dW_l
+    or db_l is the end of L chained layer products (l forward, L - l backward), each with its own
+    fp32 rounding, so |g - g_ref| <= L * (1e-5 * sum|terms| + 1e-7) with the terms of the last
+    contraction (dW_l = A_l^T dpre_l, db_l = column sums of dpre_l) from the oracle's intermediates."""
     assert abs(got["loss"] - ref.loss) <= 1e-5 * abs(ref.loss), (got["loss"], ref.loss)
     np.testing.assert_allclose(got["Z"], ref.Z[perm], rtol=0, atol=1e-4 * np.abs(ref.Z).max())
-    for l in range(len(ref.dW)):
+    L = len(ref.dW)
+    for l in range(L):
+        S = {"dW": np.abs(ref.A[l]).T @ np.abs(ref.dpre[l]), "db": np.abs(ref.dpre[l]).sum(0)}
         for k, a, r in (("dW", got["dW"][l], ref.dW[l]), ("db", got["db"][l], ref.db[l])):
-            err = np.abs(a - r).max()
-            assert np.isfinite(a).all() and err <= 1e-4 * np.abs(r).max(), (k, l, err, np.abs(r).max())
+            ratio = float((np.abs(a - r) / (L * (1e-5 * S[k] + 1e-7))).max())
+            say(k, l, "worst err/bound", ratio)
+            assert np.isfinite(a).all() and ratio <= 1.0, (k, l, ratio)
 
 
 @pytest.mark.parametrize("widths", [[24, 40, 8], [32, 64, 64, 64, 64, 16], [12, 20, 20], [8, 6, 10, 33], [16, 5]])

@@ -35,7 +35,7 @@ def random_case(seed):
     if rng.random() < 0.7 and g.nnz:
         g.vals = rng.uniform(-1.5, 1.5, size=g.nnz).astype(np.float32)
     F = int(rng.choice([1, 2, 4, 8, 12, 16, 31, 32, 64, 100, 128, 160]))
-    opts = dict(block_cap=int(rng.choice([16, 32, 64, 100, 128])), min_block=int(rng.choice([1, 4, 16])),
+    opts = dict(block_cap=int(rng.choice([16, 32, 64, 100, 128, 200, 256])), min_block=int(rng.choice([1, 4, 16])),
                 dense_density=float(rng.choice([0.05, 0.2])))
     layout = int(rng.integers(0, 2))
     return g, F, opts, layout

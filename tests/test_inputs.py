@@ -46,3 +46,18 @@ def test_ids_are_shuffled():
     g = planted_partition(16, 32, 6, 0.8, 1)
     p = g.meta["planted"]
     assert np.count_nonzero(np.diff(p) != 0) > g.n // 2     # neighbours in id are rarely co-members
+
+
+def test_rmat_graph_has_exact_edge_count_and_a_skewed_degree_distribution():
+    from ag_inputs import rmat
+    import numpy as np
+    n, m = 19717, 60000
+    g = rmat(n, m, 7)
+    assert g.n == n and g.nnz == 2 * m + n                      # both directions + the diagonal
+    rows = np.repeat(np.arange(n), np.diff(g.rowptr))
+    key = rows.astype(np.int64) * n + g.colidx
+    assert np.array_equal(np.sort(key), np.sort(g.colidx.astype(np.int64) * n + rows))   # symmetric pattern
+    deg = np.diff(g.rowptr) - 1
+    assert deg.max() > 20 * deg.mean()                          # hubs, unlike a uniform random graph
+    g2 = rmat(n, m, 7)
+    assert np.array_equal(g.colidx, g2.colidx)                  # seeded

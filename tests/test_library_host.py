@@ -169,7 +169,7 @@ def test_input_validation():
         expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, dup, None, g.n, 4, flags=1))
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n + 1, 4, flags=1))
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 0, flags=1))
-    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 4, flags=1, block_cap=129))
+    expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 4, flags=1, block_cap=257))
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 4, flags=1, method=2))
     expect_error(ag.AG_ERR_INVALID, lambda: ag.ag_plan_create(rp, ci, None, g.n, 4, flags=1, trials=16))
     p = host_plan(g)

@@ -10,7 +10,7 @@ from ag_inputs.graphs import _csr_from_directed
 
 @st.composite
 def random_matrix(draw):
-    n = draw(st.integers(1, 60))
+    n = draw(st.sampled_from([1, 2, 3, 5, 8, 13, 21, 34, 60, 150, 400]))
     m = draw(st.integers(0, 5 * n))
     seed = draw(st.integers(0, 2 ** 31 - 1))
     rng = np.random.default_rng(seed)
@@ -35,7 +35,7 @@ def random_matrix(draw):
 
 
 @settings(max_examples=150, deadline=None, suppress_health_check=[HealthCheck.too_slow])
-@given(g=random_matrix(), cap=st.integers(1, 128), minb=st.integers(1, 20), sweeps=st.integers(1, 8),
+@given(g=random_matrix(), cap=st.integers(1, 256), minb=st.integers(1, 20), sweeps=st.integers(1, 8),
        levels=st.integers(1, 12), order=st.sampled_from([-1, 1, 2, 3]), method=st.sampled_from([0, 1]))
 def test_library_equals_oracle(g, cap, minb, sweeps, levels, order, method):
     kw = dict(block_cap=cap, min_block=minb, sweeps=sweeps, max_levels=levels, order_levels=order, method=method)
