@@ -23,7 +23,7 @@ __device__ __forceinline__ void load_vec(const float *__restrict__ p, float (&h)
     }
 }
 
-#ifdef AG_EXP_NT
+// Non-temporal forms for data that is touched once (stores of finished output rows).
 template <int VEC>
 __device__ __forceinline__ void load_vec_nt(const float *__restrict__ p, float (&h)[VEC])
 {
@@ -47,7 +47,6 @@ __device__ __forceinline__ void store_vec_nt(float *__restrict__ p, const float 
         for (int j = 0; j < VEC; ++j) p[j] = h[j];
     }
 }
-#endif
 
 template <int VEC>
 __device__ __forceinline__ void store_vec(float *__restrict__ p, const float (&h)[VEC])
@@ -91,7 +90,11 @@ __device__ __forceinline__ void stage_tile(const float *__restrict__ H, int F, i
     for (int it = 0; it < ITER; ++it) {
         const int idx = tid + it * kWG, r = idx / UPR, ff = f0 + (idx % UPR) * VEC;
         if (r < nr && ff < F) {
+#if defined(AG_EXP_NT) && (AG_EXP_NT & 8)
+            load_vec_nt<VEC>(H + (size_t)(r0 + r) * F + ff, h[it]);
+#else
             load_vec<VEC>(H + (size_t)(r0 + r) * F + ff, h[it]);
+#endif
             if (scale) {
                 const float sc = scale[r0 + r];
 #pragma unroll
@@ -195,11 +198,7 @@ __device__ __forceinline__ void chunk_range_global(int c, float v, int lo, int h
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
                 if (k0 + u < hi && fok[q]) {
-#if defined(AG_EXP_NT) && (AG_EXP_NT & 2)
-                    load_vec_nt<VEC>(H + (size_t)ck[u] * F + f + q * G * VEC, h[u][q]);
-#else
                     load_vec<VEC>(H + (size_t)ck[u] * F + f + q * G * VEC, h[u][q]);
-#endif
                 } else {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) h[u][q][j] = 0.f;
