@@ -15,7 +15,7 @@ BUILD = os.path.join(HERE, "_build")
 SOURCES = ["api.cpp", "gcn.cpp", "gin.cpp", "reorder.cpp", "decompose.cpp",
            "kernels_csr.hip", "kernels_block.hip", "kernels_dense.hip", "kernels_misc.hip", "kernels_gemm.hip", "kernels_gemm_b3.hip", "kernels_coo.hip", "kernels_max.hip", "noalloc.hip"]
 
-COMMON = [*os.environ.get("AG_EXTRA_FLAGS", "").split(), "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wno-unused-result"]
 # packed fp32 VALU forms are switched off for all device code
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -81,26 +81,16 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
         c = 0;
         v = 0.f;
         if (e < ie1) {
-#if defined(AG_EXP_NT) && (AG_EXP_NT & 16)
-            c = __builtin_nontemporal_load(B.i_col8 + e);
-            v = B.i_val ? __builtin_nontemporal_load(B.i_val + e) : 1.f;
-#else
             c = B.i_col8[e];
             v = B.i_val ? B.i_val[e] : 1.f;
-#endif
         }
     };
     auto ld_r = [&](int e, int &c, float &v) {
         c = 0;
         v = 0.f;
         if (e < re1) {
-#if defined(AG_EXP_NT) && (AG_EXP_NT & 16)
-            c = __builtin_nontemporal_load(R.col + e);
-            v = R.val ? __builtin_nontemporal_load(R.val + e) : 1.f;
-#else
             c = R.col[e];
             v = R.val ? R.val[e] : 1.f;
-#endif
         }
     };
     auto begin_run = [&](int c0) {                      // row pointers and the first topology chunks of a run

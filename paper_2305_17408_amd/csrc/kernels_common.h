@@ -90,11 +90,7 @@ __device__ __forceinline__ void stage_tile(const float *__restrict__ H, int F, i
     for (int it = 0; it < ITER; ++it) {
         const int idx = tid + it * kWG, r = idx / UPR, ff = f0 + (idx % UPR) * VEC;
         if (r < nr && ff < F) {
-#if defined(AG_EXP_NT) && (AG_EXP_NT & 8)
-            load_vec_nt<VEC>(H + (size_t)(r0 + r) * F + ff, h[it]);
-#else
             load_vec<VEC>(H + (size_t)(r0 + r) * F + ff, h[it]);
-#endif
             if (scale) {
                 const float sc = scale[r0 + r];
 #pragma unroll
