@@ -110,8 +110,10 @@ typedef struct {
  * the plan will be called with.  On success *out receives a new plan. */
 int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt, ag_plan **out);
 
-/* A second plan for feature width F2 that shares the topology (host and device) of `p`;
- * it has its own selector state.  Destroy both; the topology goes with the last one. */
+/* A second plan for feature width F2 that shares the topology (host and device) of `p`: the
+ * layers of a model have different widths but one graph (Sec. 4.1: the decomposed subgraphs are
+ * passed to every layer), and the kernel choice depends on the width, so each width has its own
+ * selector state (Sec. 3.3).  Destroy both; the topology goes with the last one. */
 int ag_plan_clone_for_width(const ag_plan *p, int32_t F2, ag_plan **out);
 
 void ag_plan_destroy(ag_plan *p);
@@ -119,7 +121,13 @@ void ag_plan_destroy(ag_plan *p);
 /* ---- the hot path ----------------------------------------------------------------------- */
 
 /* Y = A.H (aggregate-sum of Sec. 2.1 with an edge value).  H, Y: device, N x F, Y is
- * overwritten and must not alias H. */
+ * overwritten and must not alias H.
+ * Finite inputs: the sparse kernels touch stored entries only (an Inf or NaN feature reaches
+ * exactly the rows that reference it), but the dense kernels AG_K_BLOCK_DENSE* multiply the
+ * non-neighbours of a block by zero, so one non-finite feature row turns every row of its
+ * diagonal block into NaN.  Which kernel runs is the selector's timing decision: with non-finite
+ * features pin AG_CLS_BLOCKS_DENSE to AG_K_BLOCK_SPARSE (ag_plan_force_kernels), or the result
+ * for the rows of that block is unspecified. */
 int ag_aggregate(ag_plan *p, const float *H_dev, float *Y_dev, void *hip_stream);
 
 /* dH = A^T.G, the backward of ag_aggregate (training, Sec. 5 "Benchmarks"). */
@@ -140,8 +148,9 @@ int ag_aggregate_t(ag_plan *p, const float *G_dev, float *dH_dev, void *hip_stre
 #define AG_STATIC_SCRATCH_BYTES (32u << 20)
 int ag_aggregate_static(ag_plan *p, const float *H_dev, float *Y_dev, void *hip_stream);
 
-/* dst[new] = src[perm[new]] (inverse == 0: caller order -> plan order) or
- * dst[perm[new]] = src[new] (inverse != 0).  N x F device matrices, no aliasing. */
+/* The paper reorders the data set once in preprocessing (Sec. 4.2, first stage): this applies the
+ * plan's vertex order to a feature matrix.  dst[new] = src[perm[new]] (inverse == 0: caller order
+ * -> plan order) or dst[perm[new]] = src[new] (inverse != 0).  N x F device matrices, no aliasing. */
 int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int32_t F,
                     int32_t inverse, void *hip_stream);
 
@@ -156,7 +165,8 @@ int ag_permute_rows(const ag_plan *p, const float *src_dev, float *dst_dev, int3
 
 /* kernels for the two block classes */
 #define AG_K_BLOCK_SPARSE     0   /* block CSR with features staged in LDS (Sec. 3.2, CSR intra) */
-#define AG_K_BLOCK_DENSE      1   /* dense tile on fp32 MFMA (Sec. 3.2, dense-based kernel)       */
+#define AG_K_BLOCK_DENSE      1   /* dense tile on fp32 MFMA (Sec. 3.2, dense-based kernel);      *
+                                   * finite features only, see ag_aggregate                        */
 #define AG_K_BLOCK_DENSE_BF16X3 2 /* the same on bf16 MFMA at fp32 accuracy: features cut into     *
                                    * three bf16 pieces that sum to them exactly; unit-weight        *
                                    * or factored matrices only (AG_ERR_UNSUPPORTED otherwise)       */
@@ -215,7 +225,8 @@ int ag_plan_profile(ag_plan *p, int32_t dir, ag_profile *out);
 
 /* ---- inspection (tests, reports) -------------------------------------------------------- */
 
-/* Host views of the decomposition, owned by the plan, valid until it is destroyed.
+/* Host views of the decomposition (Sec. 3.3 / Sec. 4.2: the reordering and the intra- and
+ * inter-community subgraphs), owned by the plan, valid until it is destroyed.
  * perm[new] = old, iperm[old] = new; diagonal block b covers plan rows
  * [blk_ptr[b], blk_ptr[b+1]); rows from blk_ptr[n_blocks] on are the tail.  The two CSR
  * parts are in plan numbering, columns ascending, values carried over unchanged. */

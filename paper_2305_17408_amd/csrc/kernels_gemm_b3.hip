@@ -3,10 +3,14 @@
 // as future work, here without giving up accuracy).
 //
 // Every fp32 operand is cut into three bf16 pieces that add up to it exactly (8 + 8 + 8 mantissa
-// bits, by truncation with the remainder computed exactly).  Of the nine piece products the six
-// with weight >= 2^-16 are accumulated in fp32, smallest first:
-//     a b ~= a3 b1 + a1 b3 + a2 b2 + a2 b1 + a1 b2 + a1 b1      (dropped terms <= 2^-23 |a b|)
-// which is the accuracy of an fp32 multiply-add chain, at 6/16 of the fp32 matrix-pipe time.
+// bits, by truncation with the remainder computed exactly, so |a2| <= 2^-7 |a| and |a3| <= 2^-14 |a|
+// in the worst case).  Of the nine piece products the six with weight >= 2^-16 are accumulated in
+// fp32, smallest first:
+//     a b ~= a3 b1 + a1 b3 + a2 b2 + a2 b1 + a1 b2 + a1 b1
+// The dropped terms a2 b3 + a3 b2 + a3 b3 are bounded by 2^-20 |a b| and reach about 2^-21 |a b|
+// (4.7e-7 |a b| for mantissas of the form 1 + 2^-7 - 2^-23); the cuts being truncations, they always point towards
+// zero (mean bias about 4e-8 |a b|): a little below the accuracy of a true fp32 product, far
+// inside the 1e-5 acceptance band, at 6/16 of the fp32 matrix-pipe time.
 // W is split once by a small kernel into K-contiguous piece rows; A is split while its tile is
 // staged into LDS.  Operand layout of v_mfma_f32_32x32x16_bf16 for lane l: A[l & 31][8 (l >> 5) +
 // 0..7], B[8 (l >> 5) + 0..7][l & 31]; result register r holds D[8 (r / 4) + 4 (l >> 5) + (r & 3)][l & 31].
