@@ -468,14 +468,35 @@ def main():
                 "algorithmic_bytes_per_launch": int(abytes),
                 "per_class_ms": {cls_names[c]: round(per_class[c], 5) for c in per_class}}
     log(f"[bench] roofline: {roofline}")
-    # the sparse-remainder kernel on its own, from the selector's timed trials (SPLIT composition)
-    rem_ms = min((t for t in sel[0]["trial_ms"][2][:2] if t > 0), default=0.0)
-    rem_bytes = algorithmic_bytes(st, F, 0, 2)
-    remainder = {"kernel": "k_csr_rows on the inter-community CSR (accumulating onto block rows)",
-                 "median_trial_ms": round(rem_ms, 5), "algorithmic_bytes_per_launch": int(rem_bytes),
-                 "achieved": round(rem_bytes / (rem_ms * 1e-3) / 1e9, 1) if rem_ms > 0 else None,
-                 "frac": round(rem_bytes / (rem_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if rem_ms > 0 else None,
-                 "unit": "GB/s", "peak": HBM_PEAK_GBS}
+    # the sparse-remainder kernel on its own: SPLIT composition pinned, HIP events around the remainder
+    # kernel (class 2) over >= 20 aggregations per direction; afterwards the frozen choice is pinned back
+    rem = {}
+    if st["nnz_inter"] > 0 and not args.pin:
+        pin(ag, plan, 0, 0, 0)
+        for _ in range(3):
+            step()
+        ag.ag_plan_set_profiling(plan, True)
+        for _ in range(max(20, args.steps // 2)):
+            step()
+        pr = [ag.ag_plan_profile(plan, d) for d in (0, 1)]
+        ag.ag_plan_set_profiling(plan, False)
+        for d in (0, 1):
+            for c in range(4):
+                ag.ag_plan_force_kernels(plan, c, d, sel[d]["choice"][c])
+        rem_ms = sum(p["class_ms"][2] for p in pr) / max(1, sum(p["calls"] for p in pr))
+        rem_bytes = algorithmic_bytes(st, F, 0, 2)
+        rem_traffic, rem_src = measured_traffic(args.config, F, [0, 0, 0, 0])
+        rem = {"kernel": "k_csr_rows (+ long-row segments) on the inter-community CSR, accumulating onto the block rows",
+               "launches_timed": sum(p["calls"] for p in pr), "avg_launch_ms": round(rem_ms, 5),
+               "traffic": rem_traffic, "traffic_source": rem_src,
+               "frac": round(rem_traffic / (rem_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if (rem_traffic and rem_ms > 0) else None,
+               "algorithmic_bytes_per_launch": int(rem_bytes),
+               "algorithmic_frac": round(rem_bytes / (rem_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if rem_ms > 0 else None,
+               "unit": "GB/s", "peak": HBM_PEAK_GBS,
+               "note": "frac = committed counter traffic of this kernel / its launch time measured in this run / peak; "
+                       "algorithmic_frac uses the no-reuse byte count instead"}
+        log(f"[bench] remainder kernel alone: {rem}")
+    remainder = rem
     compose_ms = dict(zip(("split", "fused", "full_csr", "full_csr_wide"), [round(t, 5) for t in sel[0]["trial_ms"][3][:4]]))
 
     out = {
