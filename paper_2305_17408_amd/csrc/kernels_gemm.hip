@@ -10,11 +10,11 @@
 //           transforms.  Epilogues: none, + bias then ReLU, or masking by a ReLU activation
 //           (the backward through the ReLU), fused so the N x n result is written once.
 #include "kernels_common.h"
+#include "mfma_b3.h"
 
 namespace ag {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kKSdef = 16;         // K rows staged per step
 constexpr int kMaxChunks = 512;    // K-splits (partials) per output tile
@@ -647,6 +647,8 @@ __global__ __launch_bounds__(kWG) void k_hidden_backward_mfma(const float *__res
 // tile is at once the B operand of the dW1 product: its k index runs over the block's rows in the
 // order the result registers hold them (step s: row 8 (s / 4) + 4 (l >> 5) + (s & 3)), and the A
 // operands P^T of that step are one contiguous load of P[that row][FI32 (l & 31) ...] per lane.
+// With B3 the dW1 product runs on the bf16 instruction at fp32 accuracy: the eight values a lane
+// holds for eight k-steps are cut into three bf16 pieces each and are, as they stand, its operand.
 // FI32 = f_in / 32 row tiles of dW1 per wavefront.  Every wavefront ends with its partial of
 // dW1[:, 32 columns], dW2[32 rows, :] and db1[32 columns]; fixed-order sums follow.
 template <int FI32>
@@ -657,7 +659,7 @@ struct FusedBlock {                                  // everything one wavefront
     float a[16][FI32];                               // P^T operands of the 16 k-steps of the dW1 product
 };
 
-template <int FI32>
+template <int FI32, bool B3>
 __global__ __launch_bounds__(kWG, 1) void k_gcn_backward_fused(const float *__restrict__ dQ, const float *__restrict__ W2T,
                                                             const float *__restrict__ H1, const float *__restrict__ P,
                                                             float *__restrict__ part_w1, float *__restrict__ part_w2,
@@ -737,12 +739,34 @@ __global__ __launch_bounds__(kWG, 1) void k_gcn_backward_fused(const float *__re
             d[r] = B.h[r] > 0.f ? d[r] : 0.f;
             cs += d[r];
         }
-        // dW1[32 i .. 32 i + 31][col0 .. col0 + 31] += P^T dPre: step s takes the row that register s holds
+        // dW1[rows of tile i][col0 .. col0 + 31] += P^T dPre: k-step s takes the row that register s holds
+        if constexpr (B3) {
+            // on the bf16 instruction at fp32 accuracy: sixteen k-steps are two instructions of eight, the
+            // eight values a lane holds for one of them are exactly its operand (cut into three pieces)
 #pragma unroll
-        for (int s = 0; s < 16; ++s)
+            for (int half = 0; half < 2; ++half) {
+                float dv[8];
 #pragma unroll
-            for (int i = 0; i < FI32; ++i)
-                acc1[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(B.a[s][i], d[s], acc1[i], 0, 0, 0);
+                for (int t = 0; t < 8; ++t) dv[t] = d[8 * half + t];
+                u32x4 pd[3];
+                cut3x8(dv, pd);
+#pragma unroll
+                for (int i = 0; i < FI32; ++i) {
+                    float av[8];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) av[t] = B.a[8 * half + t][i];
+                    u32x4 pa[3];
+                    cut3x8(av, pa);
+                    acc1[i] = mfma16_b3(pa, pd, acc1[i]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 16; ++s)
+#pragma unroll
+                for (int i = 0; i < FI32; ++i)
+                    acc1[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(B.a[s][i], d[s], acc1[i], 0, 0, 0);
+        }
     };
     {
         // One wavefront per SIMD with two register sets: all loads of the next block are in flight
@@ -941,7 +965,7 @@ int launch_gcn_backward_fused(int64_t N, int32_t fi, int32_t hd, int32_t c, cons
     float *p1 = scratch, *p2 = p1 + (size_t)parts * fi * hd, *pb = p2 + (size_t)parts * hd * c;
     float *stage2 = parts > kMaxChunks ? pb + (size_t)parts * hd : nullptr;
     const dim3 grid(wgs, hd == 256 ? 2 : 1);
-#define AG_FUSED(t) hipLaunchKernelGGL((k_gcn_backward_fused<t>), grid, dim3(kWG), 0, st, dQ, W2T, H1, P, p1, p2, pb, N, c, hd, kFusedRowsPerWg)
+#define AG_FUSED(t) hipLaunchKernelGGL((k_gcn_backward_fused<t, true>), grid, dim3(kWG), 0, st, dQ, W2T, H1, P, p1, p2, pb, N, c, hd, kFusedRowsPerWg)
     switch (fi / 32) {
     case 1: AG_FUSED(1); break;
     case 2: AG_FUSED(2); break;

@@ -17,33 +17,16 @@
 #include <algorithm>
 
 #include "kernels_common.h"
+#include "mfma_b3.h"
 
 namespace ag {
 namespace {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // 16 bytes of packed bf16 pieces
 
 enum { EPI_NONE = 0, EPI_BIAS_RELU = 1, EPI_RELU_MASK = 2 };
 
 constexpr int kStage = 32;              // k values staged per step (two matrix instructions deep)
 constexpr int kRowB = kStage * 2 + 16;  // bytes per LDS operand row: 64 of data + 16 of padding, so
                                         // the eight lanes of a 16-byte read phase hit distinct banks
-
-__device__ __forceinline__ floatx16 mfma16(const u32x4 &a, const u32x4 &b, const floatx16 &c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-
-__device__ __forceinline__ void cut3(float h, uint32_t (&p)[3])
-{
-    p[0] = __float_as_uint(h) & 0xffff0000u;
-    const float r1 = h - __uint_as_float(p[0]);
-    p[1] = __float_as_uint(r1) & 0xffff0000u;
-    const float r2 = r1 - __uint_as_float(p[1]);
-    p[2] = __float_as_uint(r2) & 0xffff0000u;
-}
 
 // Wp[(piece * npad + col) * kpad + kk] = piece of W[kk][col]; zero for kk >= k or col >= n
 __global__ __launch_bounds__(kWG) void k_split_w(const float *__restrict__ W, uint16_t *__restrict__ Wp,
