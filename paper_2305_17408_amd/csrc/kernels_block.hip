@@ -14,12 +14,15 @@
 // pointers of the team's rows sit in its lanes.  The kernel is bound by vector-ALU issue, not
 // by LDS or HBM, which is why a lane carries NV = 2 vectors for wide features (half the
 // shuffles and address arithmetic per FMA).
+#include <algorithm>
 #include <atomic>
 
 #include "kernels_common.h"
 
 namespace ag {
 namespace {
+
+constexpr int kWantGroups = 4096;   // work-groups a block-sparse launch should have before blocks stop being shared out
 
 // Entries lo..hi-1 of a register chunk (lane k of the team holds entry k); feature rows come
 // from the LDS tile.  Entries beyond hi belong to other rows: they are redirected to the zero
@@ -56,15 +59,20 @@ __device__ __forceinline__ void chunk_range_lds(int c, float v, int lo, int hi, 
 template <int G, int NV, int VEC, bool FUSED, bool SCALED, int MAXR>
 __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t *__restrict__ list,
                                                       CsrDev R, const float *__restrict__ H,
-                                                      float *__restrict__ Y, int F)
+                                                      float *__restrict__ Y, int F, int parts)
 {
     constexpr int FT = G * VEC * NV, TEAMS = kWG / G;
     static_assert(kMaxBlock / TEAMS + 1 <= G, "row pointers of a team must fit in its lanes");
     static_assert(MAXR % kMaxBlock == 0 && MAXR <= 256, "one-byte block-local columns");
     extern __shared__ float sH[];                       // (MAXR + 1) x FT: feature tile + a zero row
     const int tid = threadIdx.x;
-    const int b = list[xcd_contiguous(blockIdx.x, gridDim.x)];   // neighbouring blocks share an XCD (L2)
+    // `parts` work-groups share a block (each stages the whole tile and serves its share of the rows):
+    // more work-groups when a plan has few blocks.  Neighbouring ids -> the same block, the same XCD (L2).
+    const int slot = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int b = list[slot / parts];
     const int r0 = B.blk_ptr[b], nr = B.blk_ptr[b + 1] - r0;
+    const int part = slot % parts;
+    const int pr0 = (int)((long)nr * part / parts), pr1 = (int)((long)nr * (part + 1) / parts);   // this work-group's rows
     const int f0 = blockIdx.y * FT;
     const int team = tid / G, gl = tid % G;
     const int f = f0 + gl * VEC;                        // first feature of vector 0
@@ -94,7 +102,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
         }
     };
     auto begin_run = [&](int c0) {                      // row pointers and the first topology chunks of a run
-        const int cn = min(kMaxBlock, nr - c0);
+        const int cn = min(kMaxBlock, pr1 - c0);
         const int rpt = (cn + TEAMS - 1) / TEAMS;       // rows per team
         first = c0 + min(team * rpt, cn);
         myrows = min(rpt, c0 + cn - first);
@@ -115,11 +123,11 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
             ld_r(rq + 2 * G + gl, rc2, rv2);
         }
     };
-    begin_run(0);
+    begin_run(pr0);
     stage_tile<FT, VEC, MAXR>(H, F, r0, nr, nr, f0, sH, tid, SCALED ? B.in_scale : nullptr);
     for (int j = tid; j < FT; j += kWG) sH[MAXR * FT + j] = 0.f;
     __syncthreads();
-    for (int c0 = 0;;) {
+    for (int c0 = pr0;;) {
     for (int i = 0; i < myrows; ++i) {
         const int row = r0 + first + i;
         float acc[NV][VEC];
@@ -179,7 +187,7 @@ __global__ __launch_bounds__(kWG) void k_block_sparse(BlocksDev B, const int32_t
             }
     }
     c0 += kMaxBlock;
-    if (MAXR == kMaxBlock || c0 >= nr) break;           // uniform over the work-group
+    if (MAXR == kMaxBlock || c0 >= pr1) break;          // uniform over the work-group
     begin_run(c0);
     }
 }
@@ -203,8 +211,11 @@ int launch_one(const BlocksDev &B, const int32_t *list, int nlist, const CsrDev 
             if (dev >= 0 && dev < 64) prepared[dev].store(true, std::memory_order_release);
         }
     }
-    dim3 grid(nlist, (F + FT - 1) / FT);
-    hipLaunchKernelGGL((k_block_sparse<G, NV, VEC, FUSED, SCALED, MAXR>), grid, dim3(kWG), lds, st, B, list, R, H, Y, F);
+    // few blocks: up to four work-groups per block until about kWantGroups of them are in flight
+    const int tiles = (F + FT - 1) / FT;
+    const int parts = std::max(1, std::min(4, kWantGroups / std::max(1, nlist * tiles)));
+    dim3 grid(nlist * parts, tiles);
+    hipLaunchKernelGGL((k_block_sparse<G, NV, VEC, FUSED, SCALED, MAXR>), grid, dim3(kWG), lds, st, B, list, R, H, Y, F, parts);
     return hip_fail((int)hipGetLastError(), "block_sparse launch");
 }
 
