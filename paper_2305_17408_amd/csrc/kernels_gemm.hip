@@ -812,6 +812,170 @@ __global__ __launch_bounds__(kWG, 1) void k_gcn_backward_fused(const float *__re
     if (hi == 0) part_b1[pidx * hd + col0 + lo] = t;
 }
 
+// The same fused backward with the operands of the dW1 product staged through LDS: for hidden
+// widths of 128 and 256 a work-group of NW = hd / 32 wavefronts covers ALL hidden columns of a
+// block of 32 rows, so the block of P is read and cut into bf16 pieces once per work-group (8
+// values per thread) instead of once per wavefront, and the wavefronts fetch their P^T operands
+// with two 8-byte LDS reads per piece.  LDS layout of a block: sP[piece][feature][row] in bf16, a
+// feature's 32 rows taking 64 bytes of an 80-byte line (16-byte aligned 128-bit writes, lanes of a
+// read phase on distinct banks); the row order inside a line is the natural one, and the operand
+// of k-slot (hi, t) of instruction `half` is row 16 half + 8 (t / 4) + 4 hi + (t & 3): two runs of
+// four consecutive rows.  dQ goes through LDS as well (17-float lines); H1 comes straight from
+// global memory in the result layout of the instruction, one block ahead.  Two LDS buffers, one
+// barrier per block: the next block's global loads are issued before the work on the current
+// one and written to the other buffer behind it.  All loads are unconditional (clamped rows).
+template <int FI32, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void k_gcn_backward_lds(const float *__restrict__ dQ, const float *__restrict__ W2T,
+                                                                 const float *__restrict__ H1, const float *__restrict__ P,
+                                                                 float *__restrict__ part_w1, float *__restrict__ part_w2,
+                                                                 float *__restrict__ part_b1, int64_t N, int c, int rows_per_wg)
+{
+    constexpr int fi = FI32 * 32, hd = NW * 32, T = 64 * NW;
+    constexpr int kLine = 80;                              // bytes per (piece, feature) line: 32 rows x 2 + 16
+    constexpr int PV = 32 * fi / T;                        // values of the P block per thread
+    static_assert(PV == 8 || PV == 16 || PV == 4, "a thread stages whole groups of rows of one feature");
+    static_assert(T % fi == 0 || fi % T == 0, "threads map to (feature, row group)");
+    __shared__ __attribute__((aligned(16))) unsigned char sP[2][3 * fi * kLine];
+    __shared__ float sQ[2][32 * 17];
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    const int col0 = w * 32;
+    const int64_t rb = (int64_t)blockIdx.x * rows_per_wg, re = min(N, rb + rows_per_wg);
+    float bw[8];                                           // B operand of the dPre product: W2T[2 s + hi][col0 + lo]
+#pragma unroll
+    for (int s = 0; s < 8; ++s) bw[s] = (2 * s + hi < c) ? W2T[(size_t)(2 * s + hi) * hd + col0 + lo] : 0.f;
+    floatx16 acc2, acc1[FI32];
+    float cs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc2[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < FI32; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc1[i][r] = 0.f;
+
+    // staging roles: thread -> feature sf, rows sr0 .. sr0 + PV - 1 of the block (PV consecutive rows)
+    constexpr int GROUPS = 32 / PV;                        // row groups per feature
+    const int sf = tid % fi, sg = tid / fi;                // sg < GROUPS whenever T == fi * GROUPS
+    static_assert(T == fi * GROUPS, "every (feature, row group) has exactly one thread");
+    const int sr0 = sg * PV;
+    const int qrow = tid >> 2, qc4 = (tid & 3) * 4;        // dQ: the first 128 threads take one float4 each (c == 16)
+
+    float pv[PV], hn[16];
+    float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto fetch = [&](int64_t R0) {                         // global loads of block R0 into registers
+#pragma unroll
+        for (int j = 0; j < PV; ++j) {
+            const int64_t row = min(R0 + sr0 + j, N - 1);
+            pv[j] = P[row * fi + sf];
+        }
+        if (tid < 128) {
+            const int64_t row = min(R0 + qrow, N - 1);
+            if (c == 16) {
+                qv = *reinterpret_cast<const float4 *>(dQ + row * 16 + qc4);
+            } else {
+                qv.x = dQ[row * c + min(qc4, c - 1)];
+                qv.y = dQ[row * c + min(qc4 + 1, c - 1)];
+                qv.z = dQ[row * c + min(qc4 + 2, c - 1)];
+                qv.w = dQ[row * c + min(qc4 + 3, c - 1)];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = min(R0 + 8 * (r >> 2) + 4 * hi + (r & 3), N - 1);
+            hn[r] = H1[row * hd + col0 + lo];
+        }
+    };
+    auto stash = [&](int buf, int64_t R0) {                // registers -> LDS buffer, rows beyond `re` as zeros
+#pragma unroll
+        for (int j0 = 0; j0 < PV; j0 += 8) {
+            float v8[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v8[j] = (R0 + sr0 + j0 + j < re) ? pv[j0 + j] : 0.f;
+            u32x4 pc[3];
+            cut3x8(v8, pc);
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                *reinterpret_cast<u32x4 *>(&sP[buf][(s * fi + sf) * kLine + (sr0 + j0) * 2]) = pc[s];
+        }
+        if (tid < 128) {
+            const bool ok = R0 + qrow < re;
+            float *q = &sQ[buf][qrow * 17 + qc4];
+            q[0] = (ok && qc4 < c) ? qv.x : 0.f;
+            q[1] = (ok && qc4 + 1 < c) ? qv.y : 0.f;
+            q[2] = (ok && qc4 + 2 < c) ? qv.z : 0.f;
+            q[3] = (ok && qc4 + 3 < c) ? qv.w : 0.f;
+        }
+    };
+
+    float h[16];
+    int buf = 0;
+    if (rb < re) {                                         // uniform over the work-group
+        fetch(rb);
+        stash(0, rb);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) h[r] = (rb + 8 * (r >> 2) + 4 * hi + (r & 3) < re) ? hn[r] : 0.f;
+    }
+    for (int64_t R0 = rb; R0 < re; R0 += 32, buf ^= 1) {
+        __syncthreads();                                   // buffer `buf` is complete; the other one is free
+        fetch(R0 + 32);                                    // always (clamped): no branch between loads and work
+        const float *q = sQ[buf];
+        floatx16 d;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) d[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) d = __builtin_amdgcn_mfma_f32_32x32x2f32(q[lo * 17 + 2 * s + hi], bw[s], d, 0, 0, 0);
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const float b2 = q[(8 * (s >> 2) + 4 * hi + (s & 3)) * 17 + (lo & 15)];     // columns >= 16 are not stored
+            acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(h[s], b2, acc2, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            d[r] = h[r] > 0.f ? d[r] : 0.f;
+            cs += d[r];
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            float dv[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) dv[t] = d[8 * half + t];
+            u32x4 pd[3];
+            cut3x8(dv, pd);
+#pragma unroll
+            for (int i = 0; i < FI32; ++i) {
+                u32x4 pa[3];
+#pragma unroll
+                for (int s = 0; s < 3; ++s) {
+                    const unsigned char *line = &sP[buf][(s * fi + 32 * i + lo) * kLine + (16 * half + 4 * hi) * 2];
+                    const uint2 x = *reinterpret_cast<const uint2 *>(line);            // rows 16 half + 4 hi + 0..3
+                    const uint2 y = *reinterpret_cast<const uint2 *>(line + 16);       // rows 16 half + 8 + 4 hi + 0..3
+                    pa[s] = u32x4{x.x, x.y, y.x, y.y};
+                }
+                acc1[i] = mfma16_b3(pa, pd, acc1[i]);
+            }
+        }
+        stash(buf ^ 1, R0 + 32);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) h[r] = (R0 + 32 + 8 * (r >> 2) + 4 * hi + (r & 3) < re) ? hn[r] : 0.f;
+    }
+    const size_t pidx = blockIdx.x;
+    float *o2 = part_w2 + pidx * hd * c;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int m = col0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+        if (lo < c) o2[(size_t)m * c + lo] = acc2[r];
+    }
+    float *o1 = part_w1 + pidx * fi * hd;
+#pragma unroll
+    for (int i = 0; i < FI32; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = 32 * i + 8 * (r >> 2) + 4 * hi + (r & 3);
+            o1[(size_t)m * hd + col0 + lo] = acc1[i][r];
+        }
+    const float t = cs + __shfl_xor(cs, 32);
+    if (hi == 0) part_b1[pidx * hd + col0 + lo] = t;
+}
+
 inline bool hidden_backward_on_mfma(int32_t hd, int32_t c) { return (hd == 64 || hd == 128 || hd == 256) && c >= 1 && c <= 16; }
 
 constexpr int kHiddenRowsPerWg = 1024;
@@ -965,6 +1129,17 @@ int launch_gcn_backward_fused(int64_t N, int32_t fi, int32_t hd, int32_t c, cons
     float *p1 = scratch, *p2 = p1 + (size_t)parts * fi * hd, *pb = p2 + (size_t)parts * hd * c;
     float *stage2 = parts > kMaxChunks ? pb + (size_t)parts * hd : nullptr;
     const dim3 grid(wgs, hd == 256 ? 2 : 1);
+    if (fi == 128 && (hd == 128 || hd == 256)) {
+        // all hidden columns in one work-group: the P block goes through LDS, cut once
+        if (hd == 256)
+            hipLaunchKernelGGL((k_gcn_backward_lds<4, 8>), dim3(wgs), dim3(512), 0, st, dQ, W2T, H1, P, p1, p2, pb, N, c, kFusedRowsPerWg);
+        else
+            hipLaunchKernelGGL((k_gcn_backward_lds<4, 4>), dim3(wgs), dim3(256), 0, st, dQ, W2T, H1, P, p1, p2, pb, N, c, kFusedRowsPerWg);
+        sum_partials(parts, (int64_t)fi * hd, p1, dW1, stage2, st);
+        sum_partials(parts, (int64_t)hd * c, p2, dW2, stage2, st);
+        sum_partials(parts, (int64_t)hd, pb, db1, stage2, st);
+        return hip_fail((int)hipGetLastError(), "gcn_backward_lds launch");
+    }
 #define AG_FUSED(t) hipLaunchKernelGGL((k_gcn_backward_fused<t, true>), grid, dim3(kWG), 0, st, dQ, W2T, H1, P, p1, p2, pb, N, c, hd, kFusedRowsPerWg)
     switch (fi / 32) {
     case 1: AG_FUSED(1); break;

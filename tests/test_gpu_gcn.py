@@ -67,12 +67,14 @@ def test_gcn_step_small_nonsymmetric():
     compare(got, ref, perm)
 
 
-@pytest.mark.parametrize("dims", [(36, 200, 8), (128, 72, 5), (64, 136, 16), (48, 128, 10), (32, 64, 7), (40, 256, 16)])
+@pytest.mark.parametrize("dims", [(36, 200, 8), (128, 72, 5), (64, 136, 16), (48, 128, 10), (32, 64, 7), (40, 256, 16),
+                                  (128, 256, 7), (128, 128, 10), (128, 128, 16), (96, 256, 16), (64, 64, 16)])
 def test_gcn_step_ragged_widths(dims):
     # widths that are not multiples of the GEMM tiles (the wide transforms run on bf16 pieces, the
     # narrow ones on fp32 MFMA), hidden widths 64 / 128 / 256 (the backward through the second
     # transform on the matrix instruction) and others (on the vector ALUs), class counts that are
-    # not multiples of 4, vertex count not a multiple of 32 or 128
+    # not multiples of 4, vertex count not a multiple of 32 or 128; f_in = 128 with hidden 128 / 256
+    # takes the LDS-staged fused backward kernel, f_in = 32 / 64 / 96 the register-only one
     g = row_normalise(planted_partition(13, 50, 8, 0.7, 8))
     got, ref, perm = run_step(g, *dims)
     compare(got, ref, perm)
