@@ -170,12 +170,132 @@ __global__ __launch_bounds__(WVM * WVN * 64) void k_gemm_nn_b3(const float *__re
     }
 }
 
+// The same transform for k <= 128 with the weights RESIDENT IN REGISTERS: a work-group of NW =
+// ceil(n / 32) wavefronts covers all output columns of a block of 32 rows; wavefront w keeps the
+// three bf16 pieces of W[:, 32 w .. 32 w + 31] for all KT k-steps of 16 in 12 KT registers for the
+// whole kernel (the split copy Wp is K-contiguous: one 16-byte load per k-step and piece), so no
+// shared operand has to be fetched again for every tile.  The block of A is read once per
+// work-group (float4 loads, one block ahead), cut into pieces and written to LDS as
+// sA[piece][row][k] (lines of 2 KP + 16 bytes); lane (row, hi) reads its operand of a k-step with
+// one 16-byte LDS load per piece.  Two LDS buffers, one barrier per block, unconditional loads
+// with clamped rows.  (Two work-groups of four wavefronts per row block, to have them on one CU in
+// different phases, were slower: 0.52 against 0.46 ms on the 1 M x 128 x 256 transform.)  The 32 x 32 result tile gets its epilogue in registers and is stored with
+// 128-byte row pieces.
+template <int KT, int NW, int EPI>
+__global__ __launch_bounds__(64 * NW, 1) void k_gemm_nn_b3_resident(const float *__restrict__ A, const uint16_t *__restrict__ Wp,
+                                                                    float *__restrict__ C, int64_t N, int k, int kpad, int n,
+                                                                    int npad, const float *__restrict__ aux, int rows_per_wg)
+{
+    constexpr int KP = 16 * KT, T = 64 * NW, kLine = 2 * KP + 16;
+    constexpr int NV = 32 * KP / 4;                        // float4 units of a block of A
+    constexpr int UA = (NV + T - 1) / T;                   // ... per thread
+    __shared__ __attribute__((aligned(16))) unsigned char sA[2][3 * 32 * kLine];
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    const int col = 32 * w + lo;                           // < npad: Wp is zero beyond n
+    u32x4 bw[KT][3];
+#pragma unroll
+    for (int ks = 0; ks < KT; ++ks)
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+            bw[ks][s] = (16 * ks + 8 * hi < kpad)
+                            ? *reinterpret_cast<const u32x4 *>(Wp + ((size_t)s * npad + col) * kpad + 16 * ks + 8 * hi)
+                            : u32x4{0u, 0u, 0u, 0u};
+    float bias = 0.f;
+    if constexpr (EPI == EPI_BIAS_RELU) bias = col < n ? aux[col] : 0.f;
+    const int64_t rb = (int64_t)blockIdx.x * rows_per_wg, re = min(N, rb + rows_per_wg);
+    const bool vec = (k % 4 == 0);
+
+    float4 ra[UA];
+    auto fetch = [&](int64_t R0) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * T, r = idx / (KP / 4), c = (idx % (KP / 4)) * 4;
+            const int64_t row = min(R0 + min(r, 31), N - 1);
+            const float *p = A + row * k;
+            if (vec) {
+                ra[u] = *reinterpret_cast<const float4 *>(p + min(c, k - 4));
+            } else {
+                ra[u] = make_float4(p[min(c, k - 1)], p[min(c + 1, k - 1)], p[min(c + 2, k - 1)], p[min(c + 3, k - 1)]);
+            }
+        }
+    };
+    auto stash = [&](int buf, int64_t R0) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * T, r = idx / (KP / 4), c = (idx % (KP / 4)) * 4;
+            if (idx >= NV) continue;
+            const bool ok = R0 + r < re;
+            uint32_t px[3], py[3], pz[3], pw[3];
+            cut3((ok && c < k) ? ra[u].x : 0.f, px);
+            cut3((ok && c + 1 < k) ? ra[u].y : 0.f, py);
+            cut3((ok && c + 2 < k) ? ra[u].z : 0.f, pz);
+            cut3((ok && c + 3 < k) ? ra[u].w : 0.f, pw);
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                *reinterpret_cast<uint2 *>(&sA[buf][(s * 32 + r) * kLine + c * 2]) =
+                    make_uint2((px[s] >> 16) | py[s], (pz[s] >> 16) | pw[s]);
+        }
+    };
+
+    int buf = 0;
+    if (rb < re) {                                         // uniform over the work-group
+        fetch(rb);
+        stash(0, rb);
+    }
+    for (int64_t R0 = rb; R0 < re; R0 += 32, buf ^= 1) {
+        __syncthreads();                                   // buffer `buf` is complete; the other one is free
+        fetch(R0 + 32);                                    // always (clamped): no branch between loads and work
+        floatx16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KT; ++ks) {
+            u32x4 a[3];
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                a[s] = *reinterpret_cast<const u32x4 *>(&sA[buf][(s * 32 + lo) * kLine + (16 * ks + 8 * hi) * 2]);
+            acc = mfma16_b3(a, bw[ks], acc);
+        }
+        if (col < n) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = R0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+                if (row >= re) continue;
+                float v = acc[r];
+                if constexpr (EPI == EPI_BIAS_RELU) v = fmaxf(v + bias, 0.f);
+                if constexpr (EPI == EPI_RELU_MASK) v = (aux[row * n + col] > 0.f) ? v : 0.f;
+                C[row * n + col] = v;
+            }
+        }
+        stash(buf ^ 1, R0 + 32);
+    }
+}
+
+constexpr int kResidentRowsPerWg = 4096;
+
+template <int KT, int EPI>
+bool run_resident(int64_t N, int k, int kpad, int n, int npad, const float *A, const uint16_t *Wp, float *C,
+                  const float *aux, hipStream_t st)
+{
+    const int nw = (n + 31) / 32;
+    const dim3 grid((unsigned)((N + kResidentRowsPerWg - 1) / kResidentRowsPerWg));
+#define AG_RES(w) case w: hipLaunchKernelGGL((k_gemm_nn_b3_resident<KT, w, EPI>), grid, dim3(64 * w), 0, st, A, Wp, C, N, k, kpad, n, npad, aux, kResidentRowsPerWg); return true;
+    switch (nw) {                                         // the common widths; others take the tiled kernel
+    AG_RES(4) AG_RES(8)
+    default: return false;
+    }
+#undef AG_RES
+}
+
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 template <int EPI>
 void run_b3(int64_t N, int k, int n, const float *A, const uint16_t *Wp, float *C, const float *aux, hipStream_t st)
 {
     const int kpad = round_up(k, kStage), npad = round_up(n, 256);
+    // k <= 128 and up to 256 output columns: the weights stay in registers
+    if (k <= 64 && run_resident<4, EPI>(N, k, kpad, n, npad, A, Wp, C, aux, st)) return;
+    if (k > 64 && k <= 128 && run_resident<8, EPI>(N, k, kpad, n, npad, A, Wp, C, aux, st)) return;
     if (n > 128) {
         // 128 x 256 tile, 16 waves: a row tile of A is staged (and cut) once for 256 output columns
         const int ct = (n + 255) / 256;

@@ -68,7 +68,7 @@ def test_gcn_step_small_nonsymmetric():
 
 
 @pytest.mark.parametrize("dims", [(36, 200, 8), (128, 72, 5), (64, 136, 16), (48, 128, 10), (32, 64, 7), (40, 256, 16),
-                                  (128, 256, 7), (128, 128, 10), (128, 128, 16), (96, 256, 16), (64, 64, 16)])
+                                  (128, 256, 7), (128, 128, 10), (128, 128, 16), (96, 256, 16), (64, 64, 16), (100, 256, 16), (36, 128, 16), (64, 256, 9)])
 def test_gcn_step_ragged_widths(dims):
     # widths that are not multiples of the GEMM tiles (the wide transforms run on bf16 pieces, the
     # narrow ones on fp32 MFMA), hidden widths 64 / 128 / 256 (the backward through the second
