@@ -172,6 +172,8 @@ int launch_gemm_nn(int64_t N, int32_t k, int32_t n, const float *A, const float 
 size_t gemm_nn_b3_scratch_floats(int32_t k, int32_t n);
 int launch_gemm_nn_b3(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
                       const float *aux, float *wsplit, void *stream);
+int launch_gemm_chain_b3(int64_t N, int32_t k, int32_t n, int32_t c, const float *A, const float *W, const float *bias,
+                         const float *W2, float *H, float *Q, float *wsplit, void *stream);
 int launch_gemm_nn_auto(int64_t N, int32_t k, int32_t n, const float *A, const float *W, float *C, int epilogue,
                         const float *aux, float *wsplit, void *stream);
 size_t hidden_backward_scratch_floats(int64_t N, int32_t hd, int32_t c);

@@ -94,8 +94,13 @@ int ag_gcn_step(ag_plan *p_in, ag_plan *p_out, const ag_gcn_io *io, const float 
     int rc;
     // forward
     if ((rc = ag_aggregate(p_in, X, w.P, stream))) return rc;                                  // P = A X
-    if ((rc = launch_gemm_nn_auto(n, fi, hd, w.P, io->W1, w.H1, 1, io->b1, w.wsplit, stream))) return rc;     // H1 = relu(P W1 + b1)
-    if ((rc = launch_gemm_nn_auto(n, hd, c, w.H1, io->W2, w.Q, 0, nullptr, w.wsplit, stream))) return rc;     // Q = H1 W2
+    // H1 = relu(P W1 + b1) and Q = H1 W2: in one pass where the shape allows it
+    rc = launch_gemm_chain_b3(n, fi, hd, c, w.P, io->W1, io->b1, io->W2, w.H1, w.Q, w.wsplit, stream);
+    if (rc == AG_ERR_UNSUPPORTED) {
+        if ((rc = launch_gemm_nn_auto(n, fi, hd, w.P, io->W1, w.H1, 1, io->b1, w.wsplit, stream))) return rc;
+        rc = launch_gemm_nn_auto(n, hd, c, w.H1, io->W2, w.Q, 0, nullptr, w.wsplit, stream);
+    }
+    if (rc) return rc;
     if ((rc = ag_aggregate(p_out, w.Q, w.Z, stream))) return rc;                               // Z = A Q (+ b2 below)
     if ((rc = launch_softmax_xent(n, c, w.Z, io->b2, labels, io->logits, w.dZ, w.rowloss, stream))) return rc;
     if ((rc = launch_col_sum(n, 1, w.rowloss, io->loss, w.scratch, stream))) return rc;

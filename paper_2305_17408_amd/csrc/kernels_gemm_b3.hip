@@ -245,6 +245,14 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gemm_nn_b3_resident(const float 
     for (int64_t R0 = rb; R0 < re; R0 += 32, buf ^= 1) {
         __syncthreads();                                   // buffer `buf` is complete; the other one is free
         fetch(R0 + 32);                                    // always (clamped): no branch between loads and work
+        float mask[EPI == EPI_RELU_MASK ? 16 : 1];         // the mask entries travel while the matrix pipe works
+        if constexpr (EPI == EPI_RELU_MASK) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = min(R0 + 8 * (r >> 2) + 4 * hi + (r & 3), N - 1);
+                mask[r] = aux[row * n + min(col, n - 1)];
+            }
+        }
         floatx16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -263,12 +271,165 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gemm_nn_b3_resident(const float 
                 if (row >= re) continue;
                 float v = acc[r];
                 if constexpr (EPI == EPI_BIAS_RELU) v = fmaxf(v + bias, 0.f);
-                if constexpr (EPI == EPI_RELU_MASK) v = (aux[row * n + col] > 0.f) ? v : 0.f;
+                if constexpr (EPI == EPI_RELU_MASK) v = (mask[r] > 0.f) ? v : 0.f;
                 C[row * n + col] = v;
             }
         }
         stash(buf ^ 1, R0 + 32);
     }
+}
+
+// Two chained transforms of a GCN layer pair (paper Sec. 2.1, Update of layer 1 followed by the
+// product that layer 2 aggregates): H = relu(A W + b) [N x n] and Q = H W2 [N x c], c <= 16, in
+// one pass, H never being read back.  Same frame as k_gemm_nn_b3_resident (weights resident in
+// registers, the block of A cut into LDS once per work-group), with the operands of the matrix
+// instruction swapped: it then yields the TRANSPOSED tile, lane (row, hi) holding H[row][32 w +
+// 8 g + 4 hi + q] in register 4 g + q.  In that layout
+//   * a lane stores its row of the tile with four 16-byte stores, and
+//   * registers 8 s .. 8 s + 7 are, as they stand, the operand "8 consecutive k values of column
+//     `row`" of a second matrix instruction whose k index runs over the wavefront's 32 hidden
+//     columns in the order 16 s + 8 (t / 4) + 4 hi + (t & 3); the rows of W2 are loaded into the
+//     other operand in that same order, so Q^T(partial) = W2^T H^T needs no data movement at all.
+// The eight wavefronts' partial products (each over its own 32 hidden columns) meet in LDS and are
+// summed and stored by 128 threads during the next block.
+template <int KT, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void k_gemm_chain_b3(const float *__restrict__ A, const uint16_t *__restrict__ Wp,
+                                                              const float *__restrict__ bias, const float *__restrict__ W2,
+                                                              float *__restrict__ C, float *__restrict__ Q, int64_t N,
+                                                              int k, int kpad, int n, int npad, int c, int rows_per_wg)
+{
+    constexpr int KP = 16 * KT, T = 64 * NW, kLine = 2 * KP + 16;
+    constexpr int NV = 32 * KP / 4;                        // float4 units of a block of A
+    constexpr int UA = (NV + T - 1) / T;                   // ... per thread
+    constexpr int kQLine = 20;                             // floats per row of a partial Q tile: 16 + 4 of padding
+    __shared__ __attribute__((aligned(16))) unsigned char sA[2][3 * 32 * kLine];
+    __shared__ __attribute__((aligned(16))) float sQ[2][NW][32 * kQLine];
+    __shared__ __attribute__((aligned(16))) float sBias[32 * NW];
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
+    const int col = 32 * w + lo;                           // < npad: Wp is zero beyond n
+    u32x4 bw[KT][3];
+#pragma unroll
+    for (int ks = 0; ks < KT; ++ks)
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+            bw[ks][s] = (16 * ks + 8 * hi < kpad)
+                            ? *reinterpret_cast<const u32x4 *>(Wp + ((size_t)s * npad + col) * kpad + 16 * ks + 8 * hi)
+                            : u32x4{0u, 0u, 0u, 0u};
+    // W2^T operand: lane (class lo, hi), slot t of step s <-> hidden column 32 w + 16 s + 8 (t / 4) + 4 hi + (t & 3)
+    u32x4 w2p[2][3];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        float v[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int hc = 32 * w + 16 * s + 8 * (t >> 2) + 4 * hi + (t & 3);
+            v[t] = (lo < c && hc < n) ? W2[(size_t)hc * c + lo] : 0.f;
+        }
+        cut3x8(v, w2p[s]);
+    }
+    for (int i = tid; i < 32 * NW; i += T) sBias[i] = i < n ? bias[i] : 0.f;
+    const int64_t rb = (int64_t)blockIdx.x * rows_per_wg, re = min(N, rb + rows_per_wg);
+
+    float4 ra[UA];
+    auto fetch = [&](int64_t R0) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * T, r = idx / (KP / 4), cc = (idx % (KP / 4)) * 4;
+            const int64_t row = min(R0 + min(r, 31), N - 1);
+            ra[u] = *reinterpret_cast<const float4 *>(A + row * k + min(cc, k - 4));
+        }
+    };
+    auto stash = [&](int buf, int64_t R0) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int idx = tid + u * T, r = idx / (KP / 4), cc = (idx % (KP / 4)) * 4;
+            if (idx >= NV) continue;
+            const bool ok = R0 + r < re && cc < k;         // k is a multiple of 4
+            uint32_t px[3], py[3], pz[3], pw[3];
+            cut3(ok ? ra[u].x : 0.f, px);
+            cut3(ok ? ra[u].y : 0.f, py);
+            cut3(ok ? ra[u].z : 0.f, pz);
+            cut3(ok ? ra[u].w : 0.f, pw);
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                *reinterpret_cast<uint2 *>(&sA[buf][(s * 32 + r) * kLine + cc * 2]) =
+                    make_uint2((px[s] >> 16) | py[s], (pz[s] >> 16) | pw[s]);
+        }
+    };
+    // sum of the wavefronts' partial tiles of the block that started at row R0, by threads 0 .. 127
+    auto reduce_q = [&](int qbuf, int64_t R0) {
+        if (tid >= 128) return;
+        const int r = tid >> 2, c4 = (tid & 3) * 4;
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) {
+            const float4 v = *reinterpret_cast<const float4 *>(&sQ[qbuf][ww][r * kQLine + c4]);
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        const int64_t row = R0 + r;
+        if (row >= re) return;
+        float *q = Q + row * c + c4;
+        if (c % 4 == 0) {
+            if (c4 < c) *reinterpret_cast<float4 *>(q) = sum;
+        } else {
+            if (c4 < c) q[0] = sum.x;
+            if (c4 + 1 < c) q[1] = sum.y;
+            if (c4 + 2 < c) q[2] = sum.z;
+            if (c4 + 3 < c) q[3] = sum.w;
+        }
+    };
+
+    if (rb >= re) return;                                  // uniform over the work-group
+    fetch(rb);
+    stash(0, rb);
+    int buf = 0;
+    for (int64_t R0 = rb; R0 < re; R0 += 32, buf ^= 1) {
+        __syncthreads();                                   // sA[buf] and the previous block's sQ[buf ^ 1] are complete
+        fetch(R0 + 32);                                    // always (clamped): no branch between loads and work
+        if (R0 > rb) reduce_q(buf ^ 1, R0 - 32);
+        floatx16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KT; ++ks) {
+            u32x4 a[3];
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                a[s] = *reinterpret_cast<const u32x4 *>(&sA[buf][(s * 32 + lo) * kLine + (16 * ks + 8 * hi) * 2]);
+            acc = mfma16_b3(bw[ks], a, acc);               // acc[4 g + q] = (A W)[R0 + lo][32 w + 8 g + 4 hi + q]
+        }
+        const int64_t row = R0 + lo;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int hc = 32 * w + 8 * g + 4 * hi;
+            const float4 b = *reinterpret_cast<const float4 *>(&sBias[hc]);
+            acc[4 * g] = fmaxf(acc[4 * g] + b.x, 0.f);
+            acc[4 * g + 1] = fmaxf(acc[4 * g + 1] + b.y, 0.f);
+            acc[4 * g + 2] = fmaxf(acc[4 * g + 2] + b.z, 0.f);
+            acc[4 * g + 3] = fmaxf(acc[4 * g + 3] + b.w, 0.f);
+            if (row < re && hc < n)                        // n is a multiple of 4
+                *reinterpret_cast<float4 *>(C + row * n + hc) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+        }
+        floatx16 qa;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) qa[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            float v[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = acc[8 * s + t];
+            u32x4 hb[3];
+            cut3x8(v, hb);
+            qa = mfma16_b3(w2p[s], hb, qa);                // qa[4 g + q] = Q^T(partial)[class 8 g + 4 hi + q][row lo]
+        }
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+            *reinterpret_cast<float4 *>(&sQ[buf][w][lo * kQLine + 8 * g + 4 * hi]) =
+                make_float4(qa[4 * g], qa[4 * g + 1], qa[4 * g + 2], qa[4 * g + 3]);
+        stash(buf ^ 1, R0 + 32);
+    }
+    __syncthreads();
+    reduce_q(buf ^ 1, rb + ((re - rb - 1) / 32) * 32);     // the last block's partial tiles
 }
 
 constexpr int kResidentRowsPerWg = 4096;
@@ -278,10 +439,12 @@ bool run_resident(int64_t N, int k, int kpad, int n, int npad, const float *A, c
                   const float *aux, hipStream_t st)
 {
     const int nw = (n + 31) / 32;
-    const dim3 grid((unsigned)((N + kResidentRowsPerWg - 1) / kResidentRowsPerWg));
-#define AG_RES(w) case w: hipLaunchKernelGGL((k_gemm_nn_b3_resident<KT, w, EPI>), grid, dim3(64 * w), 0, st, A, Wp, C, N, k, kpad, n, npad, aux, kResidentRowsPerWg); return true;
+    // rows per work-group: about 256 x 8 wavefronts over the chip whatever the work-group's size
+    const int rows = std::max(kResidentRowsPerWg * nw / 8, 256);
+    const dim3 grid((unsigned)((N + rows - 1) / rows));
+#define AG_RES(w) case w: hipLaunchKernelGGL((k_gemm_nn_b3_resident<KT, w, EPI>), grid, dim3(64 * w), 0, st, A, Wp, C, N, k, kpad, n, npad, aux, rows); return true;
     switch (nw) {                                         // the common widths; others take the tiled kernel
-    AG_RES(4) AG_RES(8)
+    AG_RES(1) AG_RES(2) AG_RES(4) AG_RES(8)
     default: return false;
     }
 #undef AG_RES
@@ -309,11 +472,12 @@ void run_b3(int64_t N, int k, int n, const float *A, const uint16_t *Wp, float *
 
 }  // namespace
 
-// floats of scratch the split copy of W needs (0 if the shape is not served by this path: narrow
-// outputs are bound by memory, not by the matrix pipe, and stay on the fp32 kernels)
+// floats of scratch the split copy of W needs (0 if the shape is not served by this path: outputs
+// of up to 16 columns, and of up to 64 columns unless the weights fit the register-resident
+// kernel, stay on the fp32 kernels)
 size_t gemm_nn_b3_scratch_floats(int32_t k, int32_t n)
 {
-    if (k < 32 || k % 4 || n <= 64) return 0;
+    if (k < 32 || k % 4 || n <= 16 || (n <= 64 && k > 128)) return 0;
     return ((size_t)3 * round_up(n, 256) * round_up(k, kStage) * sizeof(uint16_t) + 3) / 4 + 4;
 }
 
@@ -332,6 +496,29 @@ int launch_gemm_nn_b3(int64_t N, int32_t k, int32_t n, const float *A, const flo
     else if (epilogue == EPI_RELU_MASK) run_b3<EPI_RELU_MASK>(N, k, n, A, Wp, C, aux, st);
     else run_b3<EPI_NONE>(N, k, n, A, Wp, C, aux, st);
     return hip_fail((int)hipGetLastError(), "gemm_nn_b3 launch");
+}
+
+// H = relu(A W + b) and Q = H W2 in one pass (see k_gemm_chain_b3).  `wsplit` holds at least
+// gemm_nn_b3_scratch_floats(k, n) floats.  Returns AG_ERR_UNSUPPORTED for shapes the kernel does
+// not serve: the caller then runs the two transforms one after the other.
+int launch_gemm_chain_b3(int64_t N, int32_t k, int32_t n, int32_t c, const float *A, const float *W, const float *bias,
+                         const float *W2, float *H, float *Q, float *wsplit, void *stream)
+{
+    const bool fits = wsplit && k >= 32 && k <= 128 && k % 4 == 0 && (n == 128 || n == 256) && c >= 1 && c <= 16;
+    if (!fits || gemm_nn_b3_scratch_floats(k, n) == 0) return AG_ERR_UNSUPPORTED;
+    if (N <= 0) return AG_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int kpad = round_up(k, kStage), npad = round_up(n, 256);
+    uint16_t *Wp = reinterpret_cast<uint16_t *>(wsplit);
+    const int64_t cells = (int64_t)kpad * npad;
+    hipLaunchKernelGGL(k_split_w, dim3((unsigned)((cells + kWG - 1) / kWG)), dim3(kWG), 0, st, W, Wp, k, kpad, n, npad);
+    const int nw = n / 32, rows = kResidentRowsPerWg * nw / 8;
+    const dim3 grid((unsigned)((N + rows - 1) / rows));
+#define AG_CHAIN(kt, w) hipLaunchKernelGGL((k_gemm_chain_b3<kt, w>), grid, dim3(64 * w), 0, st, A, Wp, bias, W2, H, Q, N, k, kpad, n, npad, c, rows)
+    if (k <= 64) { if (nw == 4) AG_CHAIN(4, 4); else AG_CHAIN(4, 8); }
+    else         { if (nw == 4) AG_CHAIN(8, 4); else AG_CHAIN(8, 8); }
+#undef AG_CHAIN
+    return hip_fail((int)hipGetLastError(), "gemm_chain_b3 launch");
 }
 
 // The layer transform on the fastest path that serves the shape: bf16 pieces when `wsplit` (at least
