@@ -820,7 +820,8 @@ __global__ __launch_bounds__(kWG, 1) void k_gcn_backward_fused(const float *__re
 // feature's 32 rows taking 64 bytes of an 80-byte line (16-byte aligned 128-bit writes, lanes of a
 // read phase on distinct banks); the row order inside a line is the natural one, and the operand
 // of k-slot (hi, t) of instruction `half` is row 16 half + 8 (t / 4) + 4 hi + (t & 3): two runs of
-// four consecutive rows.  dQ goes through LDS as well (17-float lines); H1 comes straight from
+// four consecutive rows.  dQ goes through LDS as well, cut into pieces, in both orientations (all
+// three products run on the bf16 instruction); H1 comes straight from
 // global memory in the result layout of the instruction, one block ahead.  Two LDS buffers, one
 // barrier per block: the next block's global loads are issued before the work on the current
 // one and written to the other buffer behind it.  All loads are unconditional (clamped rows).
@@ -836,13 +837,20 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gcn_backward_lds(const float *__
     static_assert(PV == 8 || PV == 16 || PV == 4, "a thread stages whole groups of rows of one feature");
     static_assert(T % fi == 0 || fi % T == 0, "threads map to (feature, row group)");
     __shared__ __attribute__((aligned(16))) unsigned char sP[2][3 * fi * kLine];
-    __shared__ float sQ[2][32 * 17];
+    // dQ in pieces, twice: row-major (32-byte lines: the operand of the dPre product) and
+    // class-major (80-byte lines like sP: the operand of the dW2 product)
+    __shared__ __attribute__((aligned(16))) unsigned char sQr[2][3 * 32 * 32];
+    __shared__ __attribute__((aligned(16))) unsigned char sQc[2][3 * 16 * kLine];
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lo = l & 31, hi = l >> 5;
     const int col0 = w * 32;
     const int64_t rb = (int64_t)blockIdx.x * rows_per_wg, re = min(N, rb + rows_per_wg);
-    float bw[8];                                           // B operand of the dPre product: W2T[2 s + hi][col0 + lo]
+    u32x4 w2b[3];                                          // operand of the dPre product: W2T[8 hi + t][col0 + lo], in pieces
+    {
+        float v[8];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) bw[s] = (2 * s + hi < c) ? W2T[(size_t)(2 * s + hi) * hd + col0 + lo] : 0.f;
+        for (int t = 0; t < 8; ++t) v[t] = (8 * hi + t < c) ? W2T[(size_t)(8 * hi + t) * hd + col0 + lo] : 0.f;
+        cut3x8(v, w2b);
+    }
     floatx16 acc2, acc1[FI32];
     float cs = 0.f;
 #pragma unroll
@@ -898,11 +906,21 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gcn_backward_lds(const float *__
         }
         if (tid < 128) {
             const bool ok = R0 + qrow < re;
-            float *q = &sQ[buf][qrow * 17 + qc4];
-            q[0] = (ok && qc4 < c) ? qv.x : 0.f;
-            q[1] = (ok && qc4 + 1 < c) ? qv.y : 0.f;
-            q[2] = (ok && qc4 + 2 < c) ? qv.z : 0.f;
-            q[3] = (ok && qc4 + 3 < c) ? qv.w : 0.f;
+            uint32_t q0[3], q1[3], q2[3], q3[3];
+            cut3((ok && qc4 < c) ? qv.x : 0.f, q0);
+            cut3((ok && qc4 + 1 < c) ? qv.y : 0.f, q1);
+            cut3((ok && qc4 + 2 < c) ? qv.z : 0.f, q2);
+            cut3((ok && qc4 + 3 < c) ? qv.w : 0.f, q3);
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                *reinterpret_cast<uint2 *>(&sQr[buf][(s * 32 + qrow) * 32 + qc4 * 2]) =
+                    make_uint2((q0[s] >> 16) | q1[s], (q2[s] >> 16) | q3[s]);
+                unsigned char *col = &sQc[buf][(s * 16 + qc4) * kLine + qrow * 2];
+                *reinterpret_cast<uint16_t *>(col) = (uint16_t)(q0[s] >> 16);
+                *reinterpret_cast<uint16_t *>(col + kLine) = (uint16_t)(q1[s] >> 16);
+                *reinterpret_cast<uint16_t *>(col + 2 * kLine) = (uint16_t)(q2[s] >> 16);
+                *reinterpret_cast<uint16_t *>(col + 3 * kLine) = (uint16_t)(q3[s] >> 16);
+            }
         }
     };
 
@@ -917,16 +935,30 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gcn_backward_lds(const float *__
     for (int64_t R0 = rb; R0 < re; R0 += 32, buf ^= 1) {
         __syncthreads();                                   // buffer `buf` is complete; the other one is free
         fetch(R0 + 32);                                    // always (clamped): no branch between loads and work
-        const float *q = sQ[buf];
         floatx16 d;
 #pragma unroll
         for (int r = 0; r < 16; ++r) d[r] = 0.f;
+        {
+            u32x4 qa[3];                                   // dQ[R0 + lo][8 hi + 0..7]
 #pragma unroll
-        for (int s = 0; s < 8; ++s) d = __builtin_amdgcn_mfma_f32_32x32x2f32(q[lo * 17 + 2 * s + hi], bw[s], d, 0, 0, 0);
+            for (int s = 0; s < 3; ++s) qa[s] = *reinterpret_cast<const u32x4 *>(&sQr[buf][(s * 32 + lo) * 32 + 16 * hi]);
+            d = mfma16_b3(qa, w2b, d);
+        }
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const float b2 = q[(8 * (s >> 2) + 4 * hi + (s & 3)) * 17 + (lo & 15)];     // columns >= 16 are not stored
-            acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(h[s], b2, acc2, 0, 0, 0);
+        for (int half = 0; half < 2; ++half) {             // dW2 += H1^T dQ, the block's rows in the k-slot order of the dW1 product
+            float hv[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) hv[t] = h[8 * half + t];
+            u32x4 ph[3], qb[3];
+            cut3x8(hv, ph);
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {                  // columns >= 16 of the result are not stored
+                const unsigned char *line = &sQc[buf][(s * 16 + (lo & 15)) * kLine + (16 * half + 4 * hi) * 2];
+                const uint2 x = *reinterpret_cast<const uint2 *>(line);
+                const uint2 y = *reinterpret_cast<const uint2 *>(line + 16);
+                qb[s] = u32x4{x.x, x.y, y.x, y.y};
+            }
+            acc2 = mfma16_b3(ph, qb, acc2);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
