@@ -330,21 +330,31 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gemm_chain_b3(const float *__res
     for (int i = tid; i < 32 * NW; i += T) sBias[i] = i < n ? bias[i] : 0.f;
     const int64_t rb = (int64_t)blockIdx.x * rows_per_wg, re = min(N, rb + rows_per_wg);
 
+    // Addresses advance by a constant per block (no multiplications in the loop); a load that would
+    // start beyond the last row is redirected to the last row (its values are not used).
     float4 ra[UA];
-    auto fetch = [&](int64_t R0) {
+    const float *pa[UA], *pa_last[UA];
+#pragma unroll
+    for (int u = 0; u < UA; ++u) {
+        const int idx = tid + u * T, r = idx / (KP / 4), cc = (idx % (KP / 4)) * 4;
+        pa[u] = A + (rb + min(r, 31)) * k + min(cc, k - 4);
+        pa_last[u] = A + (N - 1) * k + min(cc, k - 4);
+    }
+    const int64_t a_step = (int64_t)32 * k;
+    auto fetch = [&]() {                                   // the next block of A, in order
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
-            const int idx = tid + u * T, r = idx / (KP / 4), cc = (idx % (KP / 4)) * 4;
-            const int64_t row = min(R0 + min(r, 31), N - 1);
-            ra[u] = *reinterpret_cast<const float4 *>(A + row * k + min(cc, k - 4));
+            ra[u] = *reinterpret_cast<const float4 *>(min(pa[u], pa_last[u]));
+            pa[u] += a_step;
         }
     };
     auto stash = [&](int buf, int64_t R0) {
+        const int left = (int)min<int64_t>(re - R0, 32);   // rows of this block (<= 0: none)
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
             const int idx = tid + u * T, r = idx / (KP / 4), cc = (idx % (KP / 4)) * 4;
             if (idx >= NV) continue;
-            const bool ok = R0 + r < re && cc < k;         // k is a multiple of 4
+            const bool ok = r < left && cc < k;            // k is a multiple of 4
             uint32_t px[3], py[3], pz[3], pw[3];
             cut3(ok ? ra[u].x : 0.f, px);
             cut3(ok ? ra[u].y : 0.f, py);
@@ -357,18 +367,19 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gemm_chain_b3(const float *__res
         }
     };
     // sum of the wavefronts' partial tiles of the block that started at row R0, by threads 0 .. 127
+    float *pq = Q + (rb + (tid >> 2)) * c + (tid & 3) * 4;  // threads 0 .. 127: row tid / 4 of the block, four classes
     auto reduce_q = [&](int qbuf, int64_t R0) {
         if (tid >= 128) return;
         const int r = tid >> 2, c4 = (tid & 3) * 4;
+        float *q = pq;
+        pq += 32 * c;
         float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww) {
             const float4 v = *reinterpret_cast<const float4 *>(&sQ[qbuf][ww][r * kQLine + c4]);
             sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
         }
-        const int64_t row = R0 + r;
-        if (row >= re) return;
-        float *q = Q + row * c + c4;
+        if (R0 + r >= re) return;
         if (c % 4 == 0) {
             if (c4 < c) *reinterpret_cast<float4 *>(q) = sum;
         } else {
@@ -380,12 +391,13 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gemm_chain_b3(const float *__res
     };
 
     if (rb >= re) return;                                  // uniform over the work-group
-    fetch(rb);
+    fetch();
     stash(0, rb);
+    float *pc = C + (rb + lo) * n + 32 * w + 4 * hi;       // this lane's row of the tile; + 8 g for register group g
     int buf = 0;
     for (int64_t R0 = rb; R0 < re; R0 += 32, buf ^= 1) {
         __syncthreads();                                   // sA[buf] and the previous block's sQ[buf ^ 1] are complete
-        fetch(R0 + 32);                                    // always (clamped): no branch between loads and work
+        fetch();                                           // always (clamped): no branch between loads and work
         if (R0 > rb) reduce_q(buf ^ 1, R0 - 32);
         floatx16 acc;
 #pragma unroll
@@ -398,7 +410,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gemm_chain_b3(const float *__res
                 a[s] = *reinterpret_cast<const u32x4 *>(&sA[buf][(s * 32 + lo) * kLine + (16 * ks + 8 * hi) * 2]);
             acc = mfma16_b3(bw[ks], a, acc);               // acc[4 g + q] = (A W)[R0 + lo][32 w + 8 g + 4 hi + q]
         }
-        const int64_t row = R0 + lo;
+        const bool row_ok = lo < re - R0;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int hc = 32 * w + 8 * g + 4 * hi;
@@ -407,9 +419,10 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gemm_chain_b3(const float *__res
             acc[4 * g + 1] = fmaxf(acc[4 * g + 1] + b.y, 0.f);
             acc[4 * g + 2] = fmaxf(acc[4 * g + 2] + b.z, 0.f);
             acc[4 * g + 3] = fmaxf(acc[4 * g + 3] + b.w, 0.f);
-            if (row < re && hc < n)                        // n is a multiple of 4
-                *reinterpret_cast<float4 *>(C + row * n + hc) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+            if (row_ok && hc < n)                          // n is a multiple of 4
+                *reinterpret_cast<float4 *>(pc + 8 * g) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
         }
+        pc += (int64_t)32 * n;
         floatx16 qa;
 #pragma unroll
         for (int r = 0; r < 16; ++r) qa[r] = 0.f;
