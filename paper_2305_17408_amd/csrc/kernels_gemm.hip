@@ -817,8 +817,7 @@ __global__ __launch_bounds__(kWG, 1) void k_gcn_backward_fused(const float *__re
 // block of 32 rows, so the block of P is read and cut into bf16 pieces once per work-group (8
 // values per thread) instead of once per wavefront, and the wavefronts fetch their P^T operands
 // with two 8-byte LDS reads per piece.  LDS layout of a block: sP[piece][feature][row] in bf16, a
-// feature's 32 rows taking 64 bytes of an 80-byte line (16-byte aligned 128-bit writes, lanes of a
-// read phase on distinct banks); the row order inside a line is the natural one, and the operand
+// feature's 32 rows taking 64 bytes of a 72-byte line (lanes of a read phase on distinct banks); the row order inside a line is the natural one, and the operand
 // of k-slot (hi, t) of instruction `half` is row 16 half + 8 (t / 4) + 4 hi + (t & 3): two runs of
 // four consecutive rows.  dQ goes through LDS as well, cut into pieces, in both orientations (all
 // three products run on the bf16 instruction); H1 comes straight from
@@ -832,7 +831,10 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gcn_backward_lds(const float *__
                                                                  float *__restrict__ part_b1, int64_t N, int c, int rows_per_wg)
 {
     constexpr int fi = FI32 * 32, hd = NW * 32, T = 64 * NW;
-    constexpr int kLine = 80;                              // bytes per (piece, feature) line: 32 rows x 2 + 16
+    // bytes per (piece, feature) line: 32 rows x 2 + 8.  The 8-byte reads of the lanes (feature lo,
+    // hi = const) then start 18 banks apart: sixteen consecutive lanes cover 32 distinct banks
+    // (with 80-byte lines lanes lo and lo + 8 met in one bank and every read took two turns)
+    constexpr int kLine = 72;
     constexpr int PV = 32 * fi / T;                        // values of the P block per thread
     static_assert(PV == 8 || PV == 16 || PV == 4, "a thread stages whole groups of rows of one feature");
     static_assert(T % fi == 0 || fi % T == 0, "threads map to (feature, row group)");
@@ -902,7 +904,11 @@ __global__ __launch_bounds__(64 * NW, 1) void k_gcn_backward_lds(const float *__
             cut3x8(v8, pc);
 #pragma unroll
             for (int s = 0; s < 3; ++s)
-                *reinterpret_cast<u32x4 *>(&sP[buf][(s * fi + sf) * kLine + (sr0 + j0) * 2]) = pc[s];
+            {                                          // lines are 8-byte aligned: two 8-byte writes
+                unsigned char *d = &sP[buf][(s * fi + sf) * kLine + (sr0 + j0) * 2];
+                *reinterpret_cast<uint2 *>(d) = make_uint2(pc[s][0], pc[s][1]);
+                *reinterpret_cast<uint2 *>(d + 8) = make_uint2(pc[s][2], pc[s][3]);
+            }
         }
         if (tid < 128) {
             const bool ok = R0 + qrow < re;
