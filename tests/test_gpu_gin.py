@@ -67,7 +67,10 @@ def compare(got, ref, perm):
             assert np.isfinite(a).all() and ratio <= 1.0, (k, l, ratio)
 
 
-@pytest.mark.parametrize("widths", [[24, 40, 8], [32, 64, 64, 64, 64, 16], [12, 20, 20], [8, 6, 10, 33], [16, 5]])
+# [40, 48, 36, 12] and [64, 32, 24, 10]: transforms of 17 .. 64 output columns with k >= 32 run on the
+# register-resident bf16-pieces kernel with work-groups of two / one wavefronts, ragged in k and n
+@pytest.mark.parametrize("widths", [[24, 40, 8], [32, 64, 64, 64, 64, 16], [12, 20, 20], [8, 6, 10, 33], [16, 5],
+                                    [40, 48, 36, 12], [64, 32, 24, 10]])
 def test_gin_step_small(widths):
     # unit weights, mixed densities so the dense kernels take part; the wide-last-layer cases use
     # the aggregate-first order for the last layer, the narrow ones the transform-first order
