@@ -372,6 +372,14 @@ def main():
     st = ag.ag_plan_stats(plan)
     log(f"[bench] plan: {t_plan:.1f}s blocks={st['n_blocks']} dense={st['n_dense_blocks']} "
         f"intra={st['nnz_intra']} inter={st['nnz_inter']} long_rows={st['n_long_rows']}")
+    # the same plan from its saved reordering (what a second training on the graph pays)
+    ex = ag.ag_plan_export(plan)
+    saved = (ex["perm"].copy(), ex["blk_ptr"].copy())
+    t0 = time.time()
+    plan2 = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, F, layout=ag.AG_LAYOUT_REORDERED, reuse=saved)
+    t_plan_reuse = time.time() - t0
+    ag.ag_plan_destroy(plan2)
+    log(f"[bench] plan from a saved reordering: {t_plan_reuse:.2f}s")
 
     H = torch.from_numpy(features(g.n, F, 7)).to(dev)
     G = torch.from_numpy(features(g.n, F, 8)).to(dev)
@@ -509,7 +517,8 @@ def main():
         "medians": med,
         "effective_hbm_gbs": round(compulsory / ms_step / 1e6, 1),
         "compulsory_bytes_per_step": int(compulsory),
-        "plan_create_s": round(t_plan, 2), "selector_steps": sel_calls, "selector_s": round(t_sel, 3),
+        "plan_create_s": round(t_plan, 2), "plan_create_from_saved_reordering_s": round(t_plan_reuse, 2),
+        "selector_steps": sel_calls, "selector_s": round(t_sel, 3),
         "selector_choice": {"fwd": sel[0]["choice"], "bwd": sel[1]["choice"]},
         "plan": {**{k: st[k] for k in ("n_blocks", "n_block_rows", "n_dense_blocks", "nnz_intra", "nnz_inter",
                                        "n_long_rows", "n_long_segments", "sec_reorder", "sec_split", "sec_build",

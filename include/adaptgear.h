@@ -101,6 +101,16 @@ typedef struct {
     const float *row_scale, *col_scale;
     int32_t method;         /* community detection of the reordering, AG_METHOD_* (Sec. 4.2: the        *
                              * partitioner is the user's choice; Sec. 6.1 compares two)                  */
+    /* A reordering computed earlier (host arrays, borrowed during ag_plan_create): the perm and    *
+     * blk_ptr of an ag_plan_export of a plan of the same matrix, or the output of a partitioner of  *
+     * the caller's own (Sec. 4.2: the preprocessing is paid once per graph and reused across       *
+     * trainings).  reuse_perm[new] = old is a permutation of 0..n-1; reuse_blk_ptr has              *
+     * reuse_n_blocks + 1 ascending entries from 0 to at most n, every block of 1..256 rows; rows    *
+     * from the last entry on are the block-less tail.  When reuse_perm is given the community      *
+     * detection is skipped (block_cap, min_block, sweeps, max_levels, order_levels and method are   *
+     * then unused); anything else about the arrays is AG_ERR_INVALID.                               */
+    const int32_t *reuse_perm, *reuse_blk_ptr;
+    int32_t reuse_n_blocks;
 } ag_options;
 
 /* ---- plan life cycle -------------------------------------------------------------------- */

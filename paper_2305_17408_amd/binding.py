@@ -46,7 +46,8 @@ class ag_options(C.Structure):
                 ("layout", C.c_int32),
                 ("flags", C.c_int32), ("dense_density", C.c_float),
                 ("dev_alloc", C.c_void_p), ("dev_free", C.c_void_p), ("user", C.c_void_p),
-                ("row_scale", C.c_void_p), ("col_scale", C.c_void_p), ("method", C.c_int32)]
+                ("row_scale", C.c_void_p), ("col_scale", C.c_void_p), ("method", C.c_int32),
+                ("reuse_perm", C.c_void_p), ("reuse_blk_ptr", C.c_void_p), ("reuse_n_blocks", C.c_int32)]
 
 
 class ag_selector_info(C.Structure):
@@ -193,6 +194,14 @@ def ag_plan_create(rowptr, colidx, vals, N: int, F: int, **options):
                colidx.ctypes.data_as(_i32p), None if vals is None else vals.ctypes.data_as(_f32p))
     o = ag_options()
     keep = []                                            # host arrays borrowed by the call
+    reuse = options.pop("reuse", None)                   # (perm, blk_ptr) of an earlier ag_plan_export
+    if reuse is not None:
+        perm = np.ascontiguousarray(reuse[0], dtype=np.int32)
+        blk_ptr = np.ascontiguousarray(reuse[1], dtype=np.int32)
+        if perm.size != int(N) or blk_ptr.size < 1:
+            raise ValueError("reuse = (perm with N entries, blk_ptr with n_blocks + 1 entries)")
+        keep += [perm, blk_ptr]
+        o.reuse_perm, o.reuse_blk_ptr, o.reuse_n_blocks = perm.ctypes.data, blk_ptr.ctypes.data, int(blk_ptr.size - 1)
     for k, v in options.items():
         if not hasattr(o, k):
             raise TypeError(f"unknown option {k}")

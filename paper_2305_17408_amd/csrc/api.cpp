@@ -392,6 +392,35 @@ int aggregate_settled(ag_plan *p, const float *X, float *Y, float *partial, size
 
 }  // namespace ag
 
+namespace {
+
+// A reordering handed in by the caller: checked completely (a permutation, ascending block
+// pointers, block sizes the kernels accept) before anything is built on it.
+bool adopt_reordering(int64_t n, const int32_t *perm, const int32_t *blk_ptr, int32_t n_blocks, ag::ReorderResult &r,
+                      std::string &err)
+{
+    if (n_blocks < 0 || (n_blocks > 0 && !blk_ptr)) { err = "reuse_blk_ptr / reuse_n_blocks do not describe blocks"; return false; }
+    r.perm.assign(perm, perm + n);
+    r.iperm.assign((size_t)n, -1);
+    for (int64_t q = 0; q < n; ++q) {
+        const int32_t v = perm[q];
+        if (v < 0 || v >= n || r.iperm[v] != -1) { err = "reuse_perm is not a permutation of 0..n-1"; return false; }
+        r.iperm[v] = (int32_t)q;
+    }
+    r.blk_ptr.assign((size_t)n_blocks + 1, 0);
+    for (int32_t b = 0; b <= n_blocks; ++b) r.blk_ptr[b] = n_blocks > 0 ? blk_ptr[b] : 0;
+    if (r.blk_ptr[0] != 0 || r.blk_ptr[n_blocks] > n) { err = "reuse_blk_ptr must run from 0 to at most n"; return false; }
+    for (int32_t b = 0; b < n_blocks; ++b) {
+        const int64_t sz = (int64_t)r.blk_ptr[b + 1] - r.blk_ptr[b];
+        if (sz < 1 || sz > ag::kMaxBlockWide) { err = "reuse_blk_ptr: every block needs 1..256 rows"; return false; }
+    }
+    r.n_blocks = n_blocks;
+    r.comm.clear();
+    return true;
+}
+
+}  // namespace
+
 using namespace ag;
 
 extern "C" {
@@ -443,7 +472,12 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
         double t0 = now_sec();
         transpose_csr(A0, At);
         t->symmetric = bitwise_equal(A0, At);
-        {
+        if (o.reuse_perm) {
+            if (!adopt_reordering(t->n, o.reuse_perm, o.reuse_blk_ptr, o.reuse_n_blocks, t->r, err)) {
+                set_error(err);
+                return AG_ERR_INVALID;
+            }
+        } else {
             WGraph g;
             build_pattern_graph(A0, At, g);
             community_reorder(g, o.method, o.block_cap, o.min_block, o.sweeps, o.max_levels,
@@ -471,6 +505,7 @@ int ag_plan_create(const ag_csr *A, int64_t N, int32_t F, const ag_options *opt_
             t->factored = true;
         }
         t->opt.row_scale = t->opt.col_scale = nullptr;        // borrowed pointers are not kept
+        t->opt.reuse_perm = t->opt.reuse_blk_ptr = nullptr;
         double t2 = now_sec();
         t->sec_split = t2 - t1;
         // density classes (decided on the forward matrix; the transpose has the same counts)

@@ -55,6 +55,29 @@ def test_blocks_of_up_to_256_rows(F):
     c.close()
 
 
+def test_a_reordering_from_the_caller_with_odd_blocks():
+    # a partition handed in by the caller instead of the library's own community detection: planted
+    # communities of 90 vertices cut into blocks of 1, 256, 7, 100 and 90 rows (blocks that straddle
+    # communities, a one-row block, the largest block), the rest tail; every kernel combination
+    g = gcn_normalise(planted_partition(8, 90, 10, 0.7, 31))
+    perm = np.arange(g.n, dtype=np.int32)
+    blk = np.array([0, 1, 257, 264, 364, 454], np.int32)
+    for layout in (ag.AG_LAYOUT_ORIGINAL, ag.AG_LAYOUT_REORDERED):
+        c = Case(g, 40, seed=3, layout=layout, reuse=(perm, blk))
+        assert np.array_equal(c.exp["blk_ptr"], blk) and np.array_equal(c.exp["perm"], perm)
+        c.check_all_combos()
+        c.close()
+    # the exported reordering of a plan gives the same plan again
+    c = Case(g, 40, seed=3)
+    c2 = Case(g, 40, seed=3, reuse=(c.exp["perm"].copy(), c.exp["blk_ptr"].copy()))
+    assert np.array_equal(c.exp["intra_col"], c2.exp["intra_col"])
+    force(c.plan, "fused_narrow", 0)
+    force(c2.plan, "fused_narrow", 0)
+    assert c.torch.equal(c.forward(), c2.forward())
+    c.close()
+    c2.close()
+
+
 def test_no_blocks_at_all_and_tiny_graphs():
     # uniform sparse graph with a high min_block: every vertex lands in the tail
     g = directed_random(4000, 3.0, 79)

@@ -149,6 +149,65 @@ def test_unsorted_rows_are_sorted_and_values_follow():
     ag.ag_plan_destroy(p2)
 
 
+def test_a_saved_reordering_is_reused_and_a_foreign_one_is_split_like_the_oracle_does():
+    """A plan built from an exported (perm, blk_ptr) equals the plan they came from without running
+    the community detection; a partition of the caller's own (any permutation, any block sizes
+    up to 256) is decomposed exactly as the oracle's split decomposes it."""
+    g = gcn_normalise(planted_partition(20, 48, 6, 0.6, 4))
+    p = host_plan(g)
+    e = ag.ag_plan_export(p)
+    perm, blk = e["perm"].copy(), e["blk_ptr"].copy()
+    ag.ag_plan_destroy(p)
+    q = host_plan(g, reuse=(perm, blk))
+    try:
+        f = ag.ag_plan_export(q)
+        for k in ("perm", "iperm", "blk_ptr", "intra_rowptr", "intra_col", "inter_rowptr", "inter_col"):
+            assert np.array_equal(e[k], f[k]), k
+        assert np.array_equal(e["intra_val"].view(np.uint32), f["intra_val"].view(np.uint32))
+    finally:
+        ag.ag_plan_destroy(q)
+    # a foreign partition: rows in reverse order, blocks of 1, 256, 7 and 100 rows, the rest tail
+    rng = np.random.default_rng(5)
+    perm2 = np.arange(g.n, dtype=np.int32)[::-1].copy()
+    rng.shuffle(perm2[300:])
+    blk2 = np.array([0, 1, 257, 264, 364], np.int32)
+    iperm2 = np.empty_like(perm2)
+    iperm2[perm2] = np.arange(g.n, dtype=np.int32)
+    q = host_plan(g, reuse=(perm2, blk2))
+    try:
+        f = ag.ag_plan_export(q)
+        s = oracle.split(g.rowptr, g.colidx, g.vals, perm2, iperm2, blk2)
+        assert np.array_equal(f["perm"], perm2) and np.array_equal(f["iperm"], iperm2) and np.array_equal(f["blk_ptr"], blk2)
+        assert np.array_equal(f["intra_rowptr"], s.intra_rowptr) and np.array_equal(f["intra_col"], s.intra_col)
+        assert np.array_equal(f["inter_rowptr"], s.inter_rowptr) and np.array_equal(f["inter_col"], s.inter_col)
+        assert np.array_equal(f["intra_val"].view(np.uint32), s.intra_val.view(np.uint32))
+        assert np.array_equal(f["inter_val"].view(np.uint32), s.inter_val.view(np.uint32))
+    finally:
+        ag.ag_plan_destroy(q)
+    # no blocks at all: everything is tail
+    q = host_plan(g, reuse=(np.arange(g.n, dtype=np.int32), np.zeros(1, np.int32)))
+    st = ag.ag_plan_stats(q)
+    assert st["n_blocks"] == 0 and st["nnz_intra"] == 0 and st["nnz_inter"] == g.nnz
+    ag.ag_plan_destroy(q)
+
+
+def test_a_broken_saved_reordering_is_refused():
+    g = planted_partition(4, 40, 6, 0.6, 2)
+    ident = np.arange(g.n, dtype=np.int32)
+    ok_blk = np.array([0, 40, 80], np.int32)
+    dup = ident.copy(); dup[3] = dup[2]
+    neg = ident.copy(); neg[0] = -1
+    big = ident.copy(); big[5] = g.n
+    for perm, blk in [(dup, ok_blk), (neg, ok_blk), (big, ok_blk),
+                      (ident, np.array([1, 40], np.int32)),          # does not start at 0
+                      (ident, np.array([0, 40, 40], np.int32)),      # empty block
+                      (ident, np.array([0, 80, 40], np.int32)),      # descending
+                      (ident, np.array([0, 100, g.n + 1], np.int32))]:  # beyond n
+        expect_error(ag.AG_ERR_INVALID, lambda: host_plan(g, reuse=(perm, blk)))
+    g2 = planted_partition(3, 100, 6, 0.6, 2)
+    expect_error(ag.AG_ERR_INVALID, lambda: host_plan(g2, reuse=(np.arange(g2.n, dtype=np.int32), np.array([0, 257], np.int32))))
+
+
 def expect_error(code, fn):
     with pytest.raises(ag.AdaptGearError) as ei:
         fn()
