@@ -563,10 +563,10 @@ def main():
         loss = torch.empty(1, device=dev)
         ws = torch.empty(ag.ag_gcn_workspace_bytes(g.n, F, hid, ncls) // 4, device=dev)
 
-        def gcn():
+        def gcn(stream=None):
             ag.ag_gcn_step(plan, p_out, f_in=F, hidden=hid, n_class=ncls, W1=W1, b1=b1, W2=W2, b2=b2,
                            dW1=dW1, db1=db1, dW2=dW2, db2=db2, loss=loss, logits=None, X=Hp, labels=yl,
-                           workspace=ws)
+                           workspace=ws, stream=stream)
         n_sel = 0
         while n_sel < 60 and not (ag.ag_plan_selector_info(p_out, 0)["frozen"]
                                   and ag.ag_plan_selector_info(p_out, 1)["frozen"]):
@@ -583,6 +583,25 @@ def main():
         out["gcn_step_ms"] = round((time.perf_counter() - t0) * 1e3 / k, 4)
         out["gcn_loss"] = round(float(loss.item()), 6)
         log(f"[bench] GCN step {out['gcn_step_ms']} ms, loss {out['gcn_loss']}")
+        # the same step recorded once into a HIP graph (both plans are frozen: a step only enqueues kernels)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                gcn(side)
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["gcn_step_hip_graph_ms"] = round((time.perf_counter() - t0) * 1e3 / k, 4)
+        out["gcn_loss_hip_graph"] = round(float(loss.item()), 6)
+        log(f"[bench] GCN step as a HIP graph {out['gcn_step_hip_graph_ms']} ms, loss {out['gcn_loss_hip_graph']}")
+        del graph
         ag.ag_plan_destroy(p_out)
 
     # ms per 5-layer GIN training step (hidden 64, 16 classes) on the unit-weight GIN workload

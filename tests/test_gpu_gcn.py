@@ -104,3 +104,57 @@ def test_gcn_step_full_size_config3():
     got, ref, perm = run_step(g, 128, 256, 16)
     say("loss", got["loss"], ref.loss)
     compare(got, ref, perm)
+
+
+def test_gcn_step_replayed_from_a_hip_graph():
+    """With both plans' selectors frozen a step only enqueues kernels (no allocation, no host wait,
+    no memset nodes), so it can be recorded into a HIP graph: every replay, with eager work and
+    synchronisations in between, must reproduce the eager step bit for bit."""
+    import torch
+    dev = "cuda"
+    g = config_graph(3, scale=1 / 64)
+    fin, hid, ncls = 128, 256, 16
+    plan_in = ag.ag_plan_create(g.rowptr, g.colidx, g.vals, g.n, fin, layout=ag.AG_LAYOUT_REORDERED)
+    plan_out = ag.ag_plan_clone_for_width(plan_in, ncls)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    X, y = t(features(g.n, fin, 1)), t(labels(g.n, ncls, 2))
+    W1, W2 = t(glorot_uniform(fin, hid, 3)), t(glorot_uniform(hid, ncls, 4))
+    b1, b2 = torch.zeros(hid, device=dev), torch.zeros(ncls, device=dev)
+    outs = dict(dW1=torch.empty(fin, hid, device=dev), db1=torch.empty(hid, device=dev),
+                dW2=torch.empty(hid, ncls, device=dev), db2=torch.empty(ncls, device=dev),
+                loss=torch.empty(1, device=dev), logits=torch.empty(g.n, ncls, device=dev))
+    ws = torch.empty(ag.ag_gcn_workspace_bytes(g.n, fin, hid, ncls) // 4, device=dev)
+
+    def step(stream=None):
+        ag.ag_gcn_step(plan_in, plan_out, f_in=fin, hidden=hid, n_class=ncls, W1=W1, b1=b1, W2=W2, b2=b2, X=X,
+                       labels=y, workspace=ws, stream=stream, **outs)
+
+    n = 0
+    while n < 200 and not all(ag.ag_plan_selector_info(p, d)["frozen"] for p in (plan_in, plan_out) for d in (0, 1)):
+        step()
+        n += 1
+    say("selectors frozen after", n, "steps")
+    step()
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in outs.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for v in outs.values():
+            v.fill_(float("nan"))
+        ws.fill_(float("nan"))                               # the workspace carries nothing from step to step
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in outs.items():
+            assert torch.equal(v, eager[k]), (k, rep)
+        step()                                               # eager work between the replays
+        torch.cuda.synchronize()
+    del graph
+    ag.ag_plan_destroy(plan_out)
+    ag.ag_plan_destroy(plan_in)
