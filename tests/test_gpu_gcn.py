@@ -80,6 +80,18 @@ def test_gcn_step_ragged_widths(dims):
     compare(got, ref, perm)
 
 
+@pytest.mark.parametrize("n", [1, 5, 31, 33, 97])
+@pytest.mark.parametrize("dims", [(128, 256, 16), (128, 128, 1), (64, 256, 3), (24, 40, 8)])
+def test_gcn_step_tiny_graphs(n, dims):
+    # fewer rows than one 32-row block of the fused transform kernels, one block and a bit, a single
+    # class (loss 0, all gradients 0 but finite), a ring with self loops
+    from ag_inputs import from_edges
+    u = np.arange(n)
+    g = row_normalise(from_edges(n, u, (u + 1) % n))
+    got, ref, perm = run_step(g, *dims, seed=n)
+    compare(got, ref, perm)
+
+
 def test_gcn_step_config3_shape_scaled():
     g = config_graph(3, scale=1 / 64)
     got, ref, perm = run_step(g, 128, 256, 16)
