@@ -79,6 +79,18 @@ def test_gin_step_small(widths):
     compare(got, ref, perm)
 
 
+@pytest.mark.parametrize("n", [1, 7, 33, 130])
+@pytest.mark.parametrize("widths", [[32, 64, 64, 16], [40, 48, 36, 12], [64, 32, 1]])
+def test_gin_step_tiny_graphs(n, widths):
+    # fewer rows than one 32-row block of the transform kernels / a few blocks with a ragged tail;
+    # a unit-weight ring with self loops; a single class
+    from ag_inputs import from_edges
+    u = np.arange(n)
+    g = from_edges(n, u, (u + 1) % n)
+    got, ref, perm = run_step(g, widths, seed=n)
+    compare(got, ref, perm)
+
+
 def test_gin_step_directed_graph_with_eps():
     g = directed_random(3000, 5.0, 3, weighted=False)          # a missing transpose would show
     got, ref, perm = run_step(g, [16, 32, 32, 4], eps=0.3)
