@@ -229,3 +229,33 @@ def test_infinite_feature_reaches_only_its_neighbours():
         err = np.abs(yn[~touched] - Yfin[~touched])
         assert np.all(err <= 1e-5 * Sfin[~touched] + 1e-7), name
     c.close()
+
+
+def test_bf16_pieces_reproduce_fp32_values_bit_for_bit():
+    """The hardware side of the three-piece cut (round-to-nearest conversion, exact remainders):
+    with a permutation matrix as the dense-class block, the bf16 matrix kernel must hand every
+    feature value back unchanged, bit for bit, whatever its mantissa."""
+    import torch
+    from ag_inputs import from_edges
+    n, F = 256, 64
+    rng = np.random.default_rng(11)
+    src = np.concatenate([rng.permutation(128), 128 + rng.permutation(128)])
+    g = from_edges(n, np.arange(n), src, self_loops=False, symmetric=False)       # row i = e_src[i], unit weights
+    assert g.nnz == n and g.vals is None
+    mant = rng.integers(0, 1 << 23, size=(n, F), dtype=np.uint32)
+    mant[:, :10] = np.array([0x008000, 0x018000, 0x00FFFF, 0x007FFF, 0x008001, 0x7FFFFF, 0x000080, 0x000180,
+                             0x0080FF, 0x00807F], np.uint32)                      # ties and extremes of the rounding
+    expo = rng.integers(127 - 40, 127 + 40, size=(n, F), dtype=np.uint32)
+    sign = rng.integers(0, 2, size=(n, F), dtype=np.uint32)
+    H = ((sign << 31) | (expo << 23) | mant).view(np.float32)
+    p = ag.ag_plan_create(g.rowptr, g.colidx, None, n, F, dense_density=1e-9,
+                          reuse=(np.arange(n, dtype=np.int32), np.array([0, 128, 256], np.int32)))
+    assert ag.ag_plan_stats(p)["n_dense_blocks"] == 2
+    x = torch.from_numpy(H).cuda()
+    for name in ("split_dense_bf16x3", "fused_dense_bf16x3"):
+        force(p, name, 0)
+        y = torch.full_like(x, float("nan"))
+        ag.ag_aggregate(p, x, y)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy().view(np.uint32), H[src].view(np.uint32)), name
+    ag.ag_plan_destroy(p)
