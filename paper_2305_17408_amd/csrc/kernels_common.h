@@ -153,6 +153,29 @@ __device__ __forceinline__ void team_chunk_gather(int c, float v, int cnt, const
     }
 }
 
+// Sum of p[q * stride] for q = q0, q0 + step, ... < q1 with eight loads in flight (eight running
+// sums, combined pairwise): the additions always happen in the same order, so the result is
+// bitwise reproducible, and a reduction over a few hundred partial results does not wait for one
+// memory latency per term.
+__device__ __forceinline__ float sum_strided(const float *__restrict__ p, size_t stride, int q0, int q1, int step)
+{
+    float a[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a[u] = 0.f;
+    int q = q0;
+    for (; q + 7 * step < q1; q += 8 * step) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[(size_t)(q + u * step) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] += v[u];
+    }
+#pragma unroll
+    for (int u = 0; u < 7; ++u)
+        if (q + u * step < q1) a[u] += p[(size_t)(q + u * step) * stride];
+    return ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+}
+
 // Accumulate entries [beg,end) of one CSR row into acc, W entries per chunk (see above).
 template <int G, int W, int NV, int VEC>
 __device__ __forceinline__ void team_row_gather(const int32_t *__restrict__ col,

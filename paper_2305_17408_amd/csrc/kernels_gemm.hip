@@ -256,9 +256,7 @@ __global__ __launch_bounds__(kWG) void k_sum_partials(int nchunks, int per_group
     const int64_t i = (int64_t)blockIdx.x * 32 + (threadIdx.x & 31);
     const int slice = threadIdx.x >> 5;
     const int q0 = blockIdx.y * per_group, q1 = min(nchunks, q0 + per_group);
-    float s = 0.f;
-    if (i < count)
-        for (int q = q0 + slice; q < q1; q += 8) s += part[(size_t)q * count + i];
+    const float s = (i < count) ? sum_strided(part + i, (size_t)count, q0 + slice, q1, 8) : 0.f;
     red[threadIdx.x] = s;
     __syncthreads();
     if (threadIdx.x < 32 && i < count) {

@@ -141,9 +141,7 @@ __global__ __launch_bounds__(kWG) void k_col_sum_stage2(int nq, int f, const flo
 {
     __shared__ float red[kWG];
     const int c = blockIdx.x * 32 + (threadIdx.x & 31), slice = threadIdx.x >> 5;
-    float s = 0.f;
-    if (c < f)
-        for (int q = slice; q < nq; q += 8) s += part[(size_t)q * f + c];
+    const float s = (c < f) ? sum_strided(part + c, (size_t)f, slice, nq, 8) : 0.f;
     red[threadIdx.x] = s;
     __syncthreads();
     if (threadIdx.x < 32 && c < f) {
